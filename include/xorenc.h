@@ -1,0 +1,168 @@
+/*
+ * xorenc — decode of XOR-gate-encrypted sparse quantized weights, fused with the matrix
+ * product they feed, for AMD MI355X (gfx950).  C ABI; no C++ or framework types cross it.
+ *
+ * Method: "Structured Compression by Weight Encryption for Unstructured Pruning and
+ * Quantization" (arXiv 1905.10138).  Every n_out-bit slice w of every binary-coded bit-plane
+ * is rebuilt as w = M x over GF(2) from n_in encrypted bits x (Section 3.1), the bits listed
+ * in the slice's patch data are flipped (Section 3.2, Section 5.1), pruned positions are
+ * zeroed by the mask, the planes are dequantised as sum_p alpha[p,row] * (2 b_p - 1)
+ * (Section 3.1: multi-bit quantised weights as binary matrices) and the result multiplies a
+ * dense activation matrix (the workload of Fig. 1).
+ *
+ * General rules for every entry point:
+ *   - returns XORENC_OK (0) or a negative XORENC_E* code; never throws, aborts or prints;
+ *   - pointers marked HOST are read on the calling thread before the call returns;
+ *     pointers marked DEV are device memory owned by the caller, which must stay alive and
+ *     unchanged until the work enqueued on `hip_stream` has run; inputs are never written;
+ *   - GPU work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) of the current device; nothing synchronises and nothing allocates;
+ *   - arguments are validated on the host before any GPU call; the *contents* of device
+ *     buffers are not (use xorenc_check_packed on a host copy in tests).
+ */
+#ifndef XORENC_H
+#define XORENC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define XORENC_API __attribute__((visibility("default")))
+#else
+#define XORENC_API
+#endif
+
+#define XORENC_VERSION 0x00010000u
+
+enum {
+  XORENC_OK = 0,
+  XORENC_EINVAL = -1,       /* null pointer, negative or inconsistent size */
+  XORENC_EUNSUPPORTED = -2, /* n_out != 64, n_in not in {8,16,24,32}, q not in 1..4, unknown dtype */
+  XORENC_EALIGN = -3,       /* a device pointer or leading dimension breaks the stated alignment */
+  XORENC_EHIP = -4,         /* a HIP runtime call failed; see xorenc_last_hip_error() */
+  XORENC_EFORMAT = -5       /* xorenc_pack / xorenc_check_packed found malformed content */
+};
+
+enum { XORENC_OUT_PLANES = 0, XORENC_OUT_F32 = 1, XORENC_OUT_BF16 = 2 };
+enum { XORENC_X_F32 = 0, XORENC_X_BF16 = 1 };
+
+/* Rows are grouped in blocks of XORENC_ROWS_PER_UNIT; a "unit" is one 64-column slice
+ * position of one row block (32 slices, one per row). */
+#define XORENC_ROWS_PER_UNIT 32
+#define XORENC_N_OUT 64
+
+/*
+ * One encrypted weight matrix in the packed device layout.
+ *
+ * Logical matrix W: m rows (outputs) x n columns (inputs).  Columns are padded with pruned
+ * columns to n_pad = 64*ceil(n/64) so that a slice never straddles rows (Section 3.1 applied
+ * to the padded matrix); spr = n_pad/64 slices per row.  Rows are padded to
+ * m_pad = 32*ceil(m/32) with fully pruned rows.  Slot index of (row r, slice s):
+ *     slot(r, s) = ((r/32)*spr + s)*32 + (r % 32)            ("unit-major")
+ * so the 32 slices a unit holds are contiguous.  n_slots = m_pad*spr, n_units = n_slots/32.
+ *
+ *   mask      DEV  uint64[n_slots], 8-byte aligned.  Bit j of mask[slot(r,s)] = 1 iff weight
+ *                  (r, 64 s + j) is kept (care); padding rows/columns are 0.
+ *   enc       DEV  uint8[q][n_slots][n_in/8]: the n_in encrypted bits of each slice of each
+ *                  plane, little endian (bit j of the integer = x_j).  2-byte aligned for
+ *                  n_in = 16, 4-byte aligned for n_in = 32.
+ *   patch_off DEV  uint32[q*n_units + 1], 4-byte aligned, non-decreasing;
+ *                  entries [patch_off[p*n_units+u], patch_off[p*n_units+u+1]) belong to unit u
+ *                  of plane p.
+ *   patch     DEV  uint16[patch_off[q*n_units]], 2-byte aligned; entry = (r%32)<<6 | bit: flip
+ *                  bit `bit` (0..63) of the decrypted slice of row r%32 of that unit.  This is the
+ *                  paper's (n_patch, d_patch) re-arranged for random access: n_patch of a slice =
+ *                  number of its entries, d_patch = their bit fields.  May be NULL if there are none.
+ *   alpha     DEV  float[q][m], 4-byte aligned: per-row scale of each plane.
+ *   M_rows    HOST uint32[64]: bit j of M_rows[i] = M[i][j], the XOR-gate network (Section 3.1);
+ *                  bits >= n_in must be 0.
+ */
+typedef struct xorenc_layer {
+  uint32_t struct_size; /* = sizeof(xorenc_layer), ABI guard */
+  int32_t m, n;
+  int32_t n_out; /* 64 */
+  int32_t n_in;  /* 8, 16, 24 or 32 */
+  int32_t q;     /* 1..4 bit-planes */
+  const uint32_t *M_rows;
+  const uint8_t *enc;
+  const uint64_t *mask;
+  const uint32_t *patch_off;
+  const uint16_t *patch;
+  const float *alpha;
+} xorenc_layer;
+
+/* Element counts of the packed buffers for a shape (HOST arithmetic only). */
+typedef struct xorenc_sizes {
+  int64_t n_pad, m_pad, spr, n_slots, n_units;
+  int64_t enc_bytes;       /* q*n_slots*n_in/8 */
+  int64_t mask_words;      /* n_slots */
+  int64_t patch_off_words; /* q*n_units + 1 */
+} xorenc_sizes;
+
+XORENC_API uint32_t xorenc_version(void);
+XORENC_API const char *xorenc_strerror(int32_t code);
+/* hipError_t value of the last failed HIP call made by this library on the calling thread. */
+XORENC_API int32_t xorenc_last_hip_error(void);
+
+XORENC_API int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, xorenc_sizes *out /*HOST*/);
+
+/*
+ * Re-arrange the paper's compressed format (Section 3.2: w^c_1..l, n_patch, d_patch per plane,
+ * slices in row-major order of the column-padded matrix, l = m*spr) into the packed layout.
+ * All pointers HOST.  Pure data movement, no arithmetic of the method.
+ *   w_c      uint32[q][l]   encrypted bits of slice t = r*spr + s (bit j = x_j)
+ *   keep     uint64[l]      care mask of slice t (bit j = column 64 s + j kept)
+ *   n_patch  uint16[q][l]   number of patches of each slice
+ *   d_patch  uint8[]        bit positions, plane by plane, slice by slice, ascending within a slice;
+ *                           n_d_patch = total length = sum of n_patch
+ * Outputs sized by xorenc_get_sizes (patch: n_d_patch entries).
+ * XORENC_EFORMAT if sum(n_patch) != n_d_patch, a position is >= 64 or not ascending.
+ */
+XORENC_API int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *w_c, const uint64_t *keep,
+                    const uint16_t *n_patch, const uint8_t *d_patch, int64_t n_d_patch, uint8_t *enc_out,
+                    uint64_t *mask_out, uint32_t *patch_off_out, uint16_t *patch_out);
+
+/* Inverse of xorenc_pack (all pointers HOST; d_patch_out holds patch_off[q*n_units] bytes). */
+XORENC_API int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint8_t *enc, const uint64_t *mask,
+                      const uint32_t *patch_off, const uint16_t *patch, uint32_t *w_c_out, uint64_t *keep_out,
+                      uint16_t *n_patch_out, uint8_t *d_patch_out);
+
+/*
+ * Content check of a packed layer whose buffers are all HOST copies: offsets non-decreasing,
+ * entries sorted and unique within a unit, rows < 32, no patch on a padding row, mask zero on
+ * padding rows and columns, M_rows within n_in bits.  XORENC_EFORMAT on the first violation.
+ */
+XORENC_API int32_t xorenc_check_packed(const xorenc_layer *layer_with_host_buffers);
+
+/*
+ * Decode only (Sections 3.1-3.2 + mask + dequantisation).
+ *   XORENC_OUT_PLANES: out = DEV uint64[q][m*spr], word p*(m*spr) + r*spr + s = decrypted, patched
+ *                      slice with pruned and padding positions forced to 0; ld_out ignored.
+ *   XORENC_OUT_F32:    out = DEV float, row-major m x n, leading dimension ld_out >= n (elements):
+ *                      W[r][c] = keep ? ((+-alpha_1) + (+-alpha_2)) + ... in fp32, left to right : +0.0
+ *   XORENC_OUT_BF16:   out = DEV bf16 (uint16 patterns): round-to-nearest-even of the fp32 value.
+ * The whole output is overwritten.
+ */
+XORENC_API int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, int64_t ld_out, void *hip_stream);
+
+/*
+ * Fused decode + product: Y = W X (Fig. 1's workload on the encrypted format).
+ *   X  DEV, row-major n x B (B contiguous), leading dimension ldx >= B elements; fp32 or bf16
+ *      (uint16 patterns), aligned to its element size.
+ *   Y  DEV float, row-major m x B, leading dimension ldy >= B; overwritten.
+ * Accumulation is fp32; alpha is applied in fp32 after the contraction of each plane.  fp32 X is
+ * split exactly into three bf16 terms, so the fp32 path keeps fp32 accuracy on the matrix cores.
+ * When the launch splits the reduction dimension, partial sums meet in Y through fp32 atomics
+ * after an internal zero-fill of Y on the same stream.
+ */
+XORENC_API int32_t xorenc_spmm(const xorenc_layer *layer, const void *X, int32_t x_dtype, int64_t ldx, int32_t B, float *Y,
+                    int64_t ldy, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XORENC_H */

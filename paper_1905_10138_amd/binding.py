@@ -1,0 +1,248 @@
+"""ctypes binding of libxorenc.so: same names as the C ABI, argument marshalling only.
+
+Host-side calls (sizes, pack, unpack, check) take NumPy arrays.  GPU calls take torch tensors that
+live on the GPU; torch is used for device memory and the current stream, nothing else.  There is
+no CPU fallback: if the library is missing every call raises.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+OUT_PLANES, OUT_F32, OUT_BF16 = 0, 1, 2
+X_F32, X_BF16 = 0, 1
+
+_LIB = None
+
+
+class XorencError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = strerror(code) if _LIB is not None else str(code)
+        extra = ""
+        if code == -4 and _LIB is not None:
+            extra = f" (hipError_t {_LIB.xorenc_last_hip_error()})"
+        super().__init__(f"{where}: xorenc status {code}: {msg}{extra}")
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32), ("m", ctypes.c_int32), ("n", ctypes.c_int32),
+        ("n_out", ctypes.c_int32), ("n_in", ctypes.c_int32), ("q", ctypes.c_int32),
+        ("M_rows", ctypes.c_void_p), ("enc", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+        ("patch_off", ctypes.c_void_p), ("patch", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+    ]
+
+
+class _Sizes(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int64) for k in
+                ("n_pad", "m_pad", "spr", "n_slots", "n_units", "enc_bytes", "mask_words", "patch_off_words")]
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libxorenc.so")
+
+
+def load_library():
+    """Load libxorenc.so from the package directory (built by `python -m paper_1905_10138_amd.build`)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_1905_10138_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.xorenc_version.restype = ctypes.c_uint32
+    lib.xorenc_version.argtypes = []
+    lib.xorenc_strerror.restype = ctypes.c_char_p
+    lib.xorenc_strerror.argtypes = [i32]
+    lib.xorenc_last_hip_error.restype = i32
+    lib.xorenc_last_hip_error.argtypes = []
+    lib.xorenc_get_sizes.restype = i32
+    lib.xorenc_get_sizes.argtypes = [i32, i32, i32, i32, ctypes.POINTER(_Sizes)]
+    lib.xorenc_pack.restype = i32
+    lib.xorenc_pack.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.xorenc_unpack.restype = i32
+    lib.xorenc_unpack.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.xorenc_check_packed.restype = i32
+    lib.xorenc_check_packed.argtypes = [ctypes.POINTER(_Layer)]
+    lib.xorenc_decode.restype = i32
+    lib.xorenc_decode.argtypes = [ctypes.POINTER(_Layer), i32, vp, i64, vp]
+    lib.xorenc_spmm.restype = i32
+    lib.xorenc_spmm.argtypes = [ctypes.POINTER(_Layer), vp, i32, i64, i32, vp, i64, vp]
+    _LIB = lib
+    return lib
+
+
+def version() -> int:
+    return int(load_library().xorenc_version())
+
+
+def strerror(code: int) -> str:
+    return load_library().xorenc_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise XorencError(int(code), where)
+
+
+def get_sizes(m: int, n: int, n_in: int, q: int) -> dict:
+    s = _Sizes()
+    _check(load_library().xorenc_get_sizes(m, n, n_in, q, ctypes.byref(s)), "xorenc_get_sizes")
+    return {k: int(getattr(s, k)) for k, _ in _Sizes._fields_}
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _as(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+@dataclass
+class PackedLayer:
+    """One encrypted matrix in the packed layout; buffers are NumPy (host) or torch (device)."""
+    m: int
+    n: int
+    n_in: int
+    q: int
+    M_rows: np.ndarray            # uint32[64], always host
+    enc: object
+    mask: object
+    patch_off: object
+    patch: object
+    alpha: object
+
+    @property
+    def on_device(self) -> bool:
+        return not isinstance(self.enc, np.ndarray)
+
+    def _ptr(self, buf):
+        if buf is None:
+            return None
+        if isinstance(buf, np.ndarray):
+            return buf.ctypes.data if buf.size else None
+        return buf.data_ptr() if buf.numel() else None
+
+    def c_struct(self) -> _Layer:
+        return _Layer(ctypes.sizeof(_Layer), self.m, self.n, 64, self.n_in, self.q,
+                      self.M_rows.ctypes.data, self._ptr(self.enc), self._ptr(self.mask),
+                      self._ptr(self.patch_off), self._ptr(self.patch), self._ptr(self.alpha))
+
+    def to(self, device) -> "PackedLayer":
+        import torch
+        def mv(a, view=None):
+            t = torch.from_numpy(a.view(view) if view is not None else a)
+            return t.to(device)
+        # torch has no uint64/uint32/uint16 arithmetic needs here: move raw bytes with signed views
+        return PackedLayer(self.m, self.n, self.n_in, self.q, self.M_rows,
+                           mv(self.enc), mv(self.mask, np.int64), mv(self.patch_off, np.int32),
+                           mv(self.patch, np.int16), mv(self.alpha))
+
+    def compressed_bytes(self) -> int:
+        """Bytes of every device buffer a kernel reads for this layer."""
+        def nb(b):
+            return b.nbytes if isinstance(b, np.ndarray) else b.numel() * b.element_size()
+        return sum(nb(b) for b in (self.enc, self.mask, self.patch_off, self.patch, self.alpha))
+
+
+def pack(m, n, n_in, q, w_c, keep, n_patch, d_patch, alpha, M_rows) -> PackedLayer:
+    """xorenc_pack: paper format (host NumPy arrays) -> packed layout (host NumPy arrays)."""
+    lib = load_library()
+    sz = get_sizes(m, n, n_in, q)
+    l = m * sz["spr"]
+    w_c = _as(w_c, np.uint32).reshape(q, l)
+    keep = _as(keep, np.uint64).reshape(l)
+    n_patch = _as(n_patch, np.uint16).reshape(q, l)
+    d_patch = _as(d_patch, np.uint8).reshape(-1)
+    alpha = _as(alpha, np.float32).reshape(q, m)
+    M_rows = _as(M_rows, np.uint32).reshape(64)
+    enc = np.empty(sz["enc_bytes"], np.uint8)
+    mask = np.empty(sz["mask_words"], np.uint64)
+    patch_off = np.empty(sz["patch_off_words"], np.uint32)
+    patch = np.empty(d_patch.size, np.uint16)
+    _check(lib.xorenc_pack(m, n, n_in, q, _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
+                           _np_ptr(d_patch) if d_patch.size else None, d_patch.size, _np_ptr(enc), _np_ptr(mask),
+                           _np_ptr(patch_off), _np_ptr(patch) if patch.size else None), "xorenc_pack")
+    return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch, alpha)
+
+
+def unpack(layer: PackedLayer):
+    """xorenc_unpack on a host layer: returns (w_c uint32[q,l], keep uint64[l], n_patch uint16[q,l], d_patch uint8[])."""
+    if layer.on_device:
+        raise ValueError("unpack needs host buffers")
+    lib = load_library()
+    sz = get_sizes(layer.m, layer.n, layer.n_in, layer.q)
+    l = layer.m * sz["spr"]
+    w_c = np.empty((layer.q, l), np.uint32)
+    keep = np.empty(l, np.uint64)
+    n_patch = np.empty((layer.q, l), np.uint16)
+    d_patch = np.empty(int(layer.patch_off[-1]), np.uint8)
+    _check(lib.xorenc_unpack(layer.m, layer.n, layer.n_in, layer.q, _np_ptr(layer.enc), _np_ptr(layer.mask),
+                             _np_ptr(layer.patch_off), _np_ptr(layer.patch) if layer.patch.size else None,
+                             _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
+                             _np_ptr(d_patch) if d_patch.size else None), "xorenc_unpack")
+    return w_c, keep, n_patch, d_patch
+
+
+def check_packed(layer: PackedLayer) -> int:
+    """xorenc_check_packed on a host layer; returns the status code (0 = well formed)."""
+    if layer.on_device:
+        raise ValueError("check_packed needs host buffers")
+    st = layer.c_struct()
+    return int(load_library().xorenc_check_packed(ctypes.byref(st)))
+
+
+def _stream_ptr():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def decode(layer: PackedLayer, out_kind: int = OUT_PLANES, out=None):
+    """xorenc_decode on the current stream.  Returns the output tensor (int64 words for planes,
+    float32, or int16 bf16 patterns)."""
+    import torch
+    if not layer.on_device:
+        raise ValueError("decode needs a layer whose buffers are on the GPU")
+    dev = layer.enc.device
+    spr = (layer.n + 63) // 64
+    if out is None:
+        if out_kind == OUT_PLANES:
+            out = torch.empty((layer.q, layer.m * spr), dtype=torch.int64, device=dev)
+        elif out_kind == OUT_F32:
+            out = torch.empty((layer.m, layer.n), dtype=torch.float32, device=dev)
+        else:
+            out = torch.empty((layer.m, layer.n), dtype=torch.bfloat16, device=dev)
+    ld = out.stride(0) if out_kind != OUT_PLANES else 0
+    st = layer.c_struct()
+    _check(load_library().xorenc_decode(ctypes.byref(st), out_kind, ctypes.c_void_p(out.data_ptr()), ld,
+                                        _stream_ptr()), "xorenc_decode")
+    return out
+
+
+def spmm(layer: PackedLayer, X, Y=None):
+    """xorenc_spmm on the current stream: Y = W X with X (n, B) float32 or bfloat16, row-major."""
+    import torch
+    if not layer.on_device:
+        raise ValueError("spmm needs a layer whose buffers are on the GPU")
+    if X.dim() != 2 or X.shape[0] != layer.n or X.stride(1) != 1:
+        raise ValueError("X must be (n, B) with contiguous columns")
+    if X.dtype == torch.float32:
+        xd = X_F32
+    elif X.dtype == torch.bfloat16:
+        xd = X_BF16
+    else:
+        raise ValueError("X must be float32 or bfloat16")
+    B = X.shape[1]
+    if Y is None:
+        Y = torch.empty((layer.m, B), dtype=torch.float32, device=X.device)
+    st = layer.c_struct()
+    _check(load_library().xorenc_spmm(ctypes.byref(st), ctypes.c_void_p(X.data_ptr()), xd, X.stride(0), B,
+                                      ctypes.c_void_p(Y.data_ptr()), Y.stride(0), _stream_ptr()), "xorenc_spmm")
+    return Y

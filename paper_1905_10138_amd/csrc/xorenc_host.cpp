@@ -1,0 +1,182 @@
+// Host-only entry points of the xorenc C ABI: sizes, packing of the paper's compressed format
+// (Section 3.2 of arXiv 1905.10138: w^c_1..l, n_patch, d_patch) into the unit-major device
+// layout, its inverse, and a content checker.  No GPU calls in this file.
+#include <cstring>
+#include <vector>
+
+#include "xorenc_internal.h"
+
+extern "C" {
+
+uint32_t xorenc_version(void) { return XORENC_VERSION; }
+
+const char *xorenc_strerror(int32_t code) {
+  switch (code) {
+    case XORENC_OK: return "ok";
+    case XORENC_EINVAL: return "invalid argument (null pointer, negative or inconsistent size)";
+    case XORENC_EUNSUPPORTED: return "unsupported configuration (n_out must be 64, n_in in {8,16,24,32}, q in 1..4)";
+    case XORENC_EALIGN: return "misaligned pointer or leading dimension";
+    case XORENC_EHIP: return "HIP runtime call failed";
+    case XORENC_EFORMAT: return "malformed compressed data";
+    default: return "unknown xorenc status";
+  }
+}
+
+int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, xorenc_sizes *out) {
+  if (!out || m <= 0 || n <= 0) return XORENC_EINVAL;
+  if (!(n_in == 8 || n_in == 16 || n_in == 24 || n_in == 32) || q < 1 || q > XORENC_MAX_Q) return XORENC_EUNSUPPORTED;
+  const int64_t spr = ((int64_t)n + 63) / 64;
+  const int64_t nrb = ((int64_t)m + 31) / 32;
+  out->n_pad = spr * 64;
+  out->m_pad = nrb * 32;
+  out->spr = spr;
+  out->n_slots = nrb * 32 * spr;
+  out->n_units = nrb * spr;
+  out->enc_bytes = (int64_t)q * out->n_slots * (n_in / 8);
+  out->mask_words = out->n_slots;
+  out->patch_off_words = (int64_t)q * out->n_units + 1;
+  return XORENC_OK;
+}
+
+int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *w_c, const uint64_t *keep,
+                    const uint16_t *n_patch, const uint8_t *d_patch, int64_t n_d_patch, uint8_t *enc_out,
+                    uint64_t *mask_out, uint32_t *patch_off_out, uint16_t *patch_out) {
+  xorenc_sizes sz;
+  int32_t rc = xorenc_get_sizes(m, n, n_in, q, &sz);
+  if (rc != XORENC_OK) return rc;
+  if (!w_c || !keep || !n_patch || !enc_out || !mask_out || !patch_off_out || n_d_patch < 0) return XORENC_EINVAL;
+  if (n_d_patch > 0 && (!d_patch || !patch_out)) return XORENC_EINVAL;
+  const int64_t spr = sz.spr, l = (int64_t)m * spr;
+  const int nib = n_in / 8;
+  std::memset(enc_out, 0, (size_t)sz.enc_bytes);
+  std::memset(mask_out, 0, (size_t)sz.mask_words * sizeof(uint64_t));
+
+  // start of every slice's d_patch run inside each plane's stream
+  std::vector<int64_t> start((size_t)q * l + 1);
+  int64_t run = 0;
+  for (int64_t i = 0; i < (int64_t)q * l; ++i) {
+    start[i] = run;
+    run += n_patch[i];
+  }
+  start[(size_t)q * l] = run;
+  if (run != n_d_patch) return XORENC_EFORMAT;
+
+  int64_t w = 0;  // write cursor in patch_out
+  for (int p = 0; p < q; ++p) {
+    for (int64_t u = 0; u < sz.n_units; ++u) {
+      patch_off_out[(int64_t)p * sz.n_units + u] = (uint32_t)w;
+      const int64_t rb = u / spr, s = u % spr;
+      for (int rr = 0; rr < 32; ++rr) {
+        const int64_t r = rb * 32 + rr;
+        if (r >= m) break;
+        const int64_t t = r * spr + s;               // paper order
+        const int64_t slot = u * 32 + rr;            // packed order
+        if (p == 0) mask_out[slot] = keep[t];
+        const uint32_t x = w_c[(int64_t)p * l + t];
+        if (n_in < 32 && (x >> n_in)) return XORENC_EFORMAT;
+        for (int b = 0; b < nib; ++b) enc_out[((int64_t)p * sz.n_slots + slot) * nib + b] = (uint8_t)(x >> (8 * b));
+        const int64_t a = start[(int64_t)p * l + t], e = start[(int64_t)p * l + t + 1];
+        int prev = -1;
+        for (int64_t i = a; i < e; ++i) {
+          const int bit = d_patch[i];
+          if (bit >= 64 || bit <= prev) return XORENC_EFORMAT;
+          prev = bit;
+          patch_out[w++] = (uint16_t)((rr << 6) | bit);
+        }
+      }
+    }
+  }
+  patch_off_out[(int64_t)q * sz.n_units] = (uint32_t)w;
+  return w == n_d_patch ? XORENC_OK : XORENC_EFORMAT;
+}
+
+int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint8_t *enc, const uint64_t *mask,
+                      const uint32_t *patch_off, const uint16_t *patch, uint32_t *w_c_out, uint64_t *keep_out,
+                      uint16_t *n_patch_out, uint8_t *d_patch_out) {
+  xorenc_sizes sz;
+  int32_t rc = xorenc_get_sizes(m, n, n_in, q, &sz);
+  if (rc != XORENC_OK) return rc;
+  if (!enc || !mask || !patch_off || !w_c_out || !keep_out || !n_patch_out) return XORENC_EINVAL;
+  const int64_t spr = sz.spr, l = (int64_t)m * spr;
+  const int nib = n_in / 8;
+  const int64_t total = patch_off[(int64_t)q * sz.n_units];
+  if (total > 0 && (!patch || !d_patch_out)) return XORENC_EINVAL;
+  // pass 1: per-slice counts and the other streams
+  std::memset(n_patch_out, 0, (size_t)q * l * sizeof(uint16_t));
+  for (int p = 0; p < q; ++p)
+    for (int64_t u = 0; u < sz.n_units; ++u) {
+      const int64_t rb = u / spr, s = u % spr;
+      for (int rr = 0; rr < 32; ++rr) {
+        const int64_t r = rb * 32 + rr;
+        if (r >= m) break;
+        const int64_t t = r * spr + s, slot = u * 32 + rr;
+        if (p == 0) keep_out[t] = mask[slot];
+        uint32_t x = 0;
+        for (int b = 0; b < nib; ++b) x |= (uint32_t)enc[((int64_t)p * sz.n_slots + slot) * nib + b] << (8 * b);
+        w_c_out[(int64_t)p * l + t] = x;
+      }
+      const uint32_t a = patch_off[(int64_t)p * sz.n_units + u], e = patch_off[(int64_t)p * sz.n_units + u + 1];
+      if (e < a || e > total) return XORENC_EFORMAT;
+      for (uint32_t i = a; i < e; ++i) {
+        const int64_t r = rb * 32 + (patch[i] >> 6);
+        if ((patch[i] >> 6) >= 32 || r >= m) return XORENC_EFORMAT;
+        n_patch_out[(int64_t)p * l + r * spr + s]++;
+      }
+    }
+  // pass 2: scatter the bit positions into paper order
+  std::vector<int64_t> cur((size_t)q * l);
+  int64_t run = 0;
+  for (int64_t i = 0; i < (int64_t)q * l; ++i) {
+    cur[i] = run;
+    run += n_patch_out[i];
+  }
+  for (int p = 0; p < q; ++p)
+    for (int64_t u = 0; u < sz.n_units; ++u) {
+      const int64_t rb = u / spr, s = u % spr;
+      const uint32_t a = patch_off[(int64_t)p * sz.n_units + u], e = patch_off[(int64_t)p * sz.n_units + u + 1];
+      for (uint32_t i = a; i < e; ++i) {
+        const int64_t r = rb * 32 + (patch[i] >> 6);
+        d_patch_out[cur[(int64_t)p * l + r * spr + s]++] = (uint8_t)(patch[i] & 63);
+      }
+    }
+  return XORENC_OK;
+}
+
+int32_t xorenc_check_packed(const xorenc_layer *L) {
+  if (!L || L->struct_size != sizeof(xorenc_layer)) return XORENC_EINVAL;
+  if (L->n_out != XORENC_N_OUT) return XORENC_EUNSUPPORTED;
+  xorenc_sizes sz;
+  int32_t rc = xorenc_get_sizes(L->m, L->n, L->n_in, L->q, &sz);
+  if (rc != XORENC_OK) return rc;
+  if (!L->M_rows || !L->enc || !L->mask || !L->patch_off || !L->alpha) return XORENC_EINVAL;
+  for (int i = 0; i < 64; ++i)
+    if (L->n_in < 32 && (L->M_rows[i] >> L->n_in)) return XORENC_EFORMAT;
+  const int64_t spr = sz.spr;
+  const int tail = (int)(L->n - (spr - 1) * 64);  // valid columns in the last slice of a row
+  for (int64_t u = 0; u < sz.n_units; ++u) {
+    const int64_t rb = u / spr, s = u % spr;
+    for (int rr = 0; rr < 32; ++rr) {
+      const uint64_t w = L->mask[u * 32 + rr];
+      if (rb * 32 + rr >= L->m && w) return XORENC_EFORMAT;
+      if (s == spr - 1 && tail < 64 && (w >> tail)) return XORENC_EFORMAT;
+    }
+  }
+  const int64_t noff = (int64_t)L->q * sz.n_units;
+  if (L->patch_off[0] != 0) return XORENC_EFORMAT;
+  if (L->patch_off[noff] > 0 && !L->patch) return XORENC_EINVAL;
+  for (int64_t i = 0; i < noff; ++i) {
+    const uint32_t a = L->patch_off[i], e = L->patch_off[i + 1];
+    if (e < a) return XORENC_EFORMAT;
+    const int64_t u = i % sz.n_units, rb = u / spr;
+    int prev = -1;
+    for (uint32_t k = a; k < e; ++k) {
+      const int v = L->patch[k];
+      if (v <= prev || (v >> 6) >= 32 || rb * 32 + (v >> 6) >= L->m) return XORENC_EFORMAT;
+      if (!((L->mask[u * 32 + (v >> 6)] >> (v & 63)) & 1)) return XORENC_EFORMAT;  // patches sit on care bits
+      prev = v;
+    }
+  }
+  return XORENC_OK;
+}
+
+}  // extern "C"

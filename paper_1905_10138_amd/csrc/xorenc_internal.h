@@ -1,0 +1,10 @@
+// Internal declarations shared by the host-side and device-side sources of libxorenc.
+#ifndef XORENC_INTERNAL_H
+#define XORENC_INTERNAL_H
+
+#include "../../include/xorenc.h"
+
+#define XORENC_MAX_Q 4
+#define XORENC_MAX_N_IN 32
+
+#endif

@@ -1,0 +1,78 @@
+"""GPU parity of xorenc_decode against the CPU oracle: bit-exact planes, fp32 and bf16 dense output."""
+import numpy as np
+import pytest
+
+from helpers import encoded_workload, pack_encoded
+from oracle import decoder, gf2
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [("tiny", 256, 256), ("fig1", 200, 448), ("fc6", 97, 640), ("lstm", 130, 3000),
+         ("large_q1", 320, 1024), ("large_q2", 96, 4096), ("lstm", 1, 64), ("tiny", 33, 70)]
+FULL = [("fig1", None, None), ("fc6", None, None), ("lstm", None, None), ("large_q1", None, None),
+        ("large_q2", None, None)]
+
+
+def _gpu_layer(name, m, n):
+    import torch
+    wl, enc = encoded_workload(name, m, n)
+    return wl, enc, pack_encoded(enc).to(torch.device("cuda:0"))
+
+
+@pytest.mark.parametrize("name,m,n", SMALL + FULL)
+def test_planes_bit_exact(name, m, n):
+    import paper_1905_10138_amd as xe
+    wl, enc, L = _gpu_layer(name, m, n)
+    got = xe.decode(L, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
+    want = decoder.pack_planes_u64(decoder.masked_planes(enc))
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+    # lossless: the decoded planes are the quantiser's bits on every kept position
+    assert np.array_equal(want, decoder.pack_planes_u64(wl.planes))
+
+
+@pytest.mark.parametrize("name,m,n", SMALL + FULL[:1] + FULL[2:4])
+def test_dense_f32_and_bf16_bit_exact(name, m, n):
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc, L = _gpu_layer(name, m, n)
+    want = decoder.dequantize_f32(enc)
+    got = xe.decode(L, xe.OUT_F32).cpu().numpy()
+    assert got.shape == want.shape
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    got16 = xe.decode(L, xe.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(want))
+
+
+def test_dense_output_with_leading_dimension_leaves_padding_untouched():
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc, L = _gpu_layer("lstm", 130, 3000)
+    buf = torch.full((130, 3100), 7.0, dtype=torch.float32, device="cuda:0")
+    xe.decode(L, xe.OUT_F32, out=buf[:, :3000])
+    got = buf.cpu().numpy()
+    assert np.array_equal(got[:, :3000], decoder.dequantize_f32(enc))
+    assert np.all(got[:, 3000:] == 7.0)
+
+
+def test_unit_inputs_decode_to_columns_of_M():
+    """Property that needs no oracle: with w^c = e_j, all-ones mask and no patches the decoded slice is column j of M."""
+    import torch
+    import paper_1905_10138_amd as xe
+    rng = np.random.default_rng(5)
+    n_in, m, n = 24, 64, 64 * n_in
+    M = rng.integers(0, 2, size=(64, n_in), dtype=np.uint8)
+    spr = n // 64
+    w_c = np.tile((np.uint32(1) << np.arange(n_in, dtype=np.uint32)), m)[None]      # slice s of every row: e_s
+    keep = np.full(m * spr, np.uint64(0xFFFFFFFFFFFFFFFF))
+    L = xe.pack(m, n, n_in, 1, w_c, keep, np.zeros((1, m * spr), np.uint16), np.zeros(0, np.uint8),
+                np.ones((1, m), np.float32), gf2.bits_to_int(M).astype(np.uint32)).to(torch.device("cuda:0"))
+    got = xe.decode(L, xe.OUT_PLANES).cpu().numpy().view(np.uint64).reshape(m, spr)
+    cols = gf2.bits_to_int(M.T)                      # column j as a 64-bit word
+    assert np.array_equal(got, np.tile(cols, (m, 1)))
+    # linearity: w^c = e_a ^ e_b decodes to the XOR of two columns
+    w2 = np.full((1, m * spr), np.uint32(0b101), np.uint32)
+    L2 = xe.pack(m, n, n_in, 1, w2, keep, np.zeros((1, m * spr), np.uint16), np.zeros(0, np.uint8),
+                 np.ones((1, m), np.float32), gf2.bits_to_int(M).astype(np.uint32)).to(torch.device("cuda:0"))
+    got2 = xe.decode(L2, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
+    assert np.all(got2 == (cols[0] ^ cols[2]))

@@ -1,0 +1,111 @@
+"""GPU parity of the fused decode + product (xorenc_spmm) against the fp64 oracle.
+
+Tolerances (relative Frobenius error against fp64): 2e-3 for bf16 X, 1e-5 for fp32 X.  The
+kernel multiplies exact +-2/0 operands with exact bf16 terms and accumulates in fp32, so the
+observed error is far below both; the bounds are the contract, not the expectation."""
+import numpy as np
+import pytest
+
+from helpers import encoded_workload, pack_encoded, rel_fro
+from oracle import decoder
+from synth_inputs import draw_X
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+
+
+def _run(name, m, n, B, dtype, ldx_pad=0):
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc = encoded_workload(name, m, n)
+    L = pack_encoded(enc).to(torch.device("cuda:0"))
+    stored, exact = draw_X(wl.n, B, dtype, wl.cfg.seed_X + 1000 * B)
+    if dtype == "bf16":
+        xt = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16)
+    else:
+        xt = torch.from_numpy(stored)
+    if ldx_pad:
+        buf = torch.zeros((wl.n, B + ldx_pad), dtype=xt.dtype)
+        buf[:, :B] = xt
+        xg = buf.to("cuda:0")[:, :B]
+    else:
+        xg = xt.to("cuda:0")
+    Y = xe.spmm(L, xg)
+    torch.cuda.synchronize()
+    want = decoder.spmm_f64(enc, exact)
+    return Y.cpu().numpy(), want
+
+
+SMALL_CASES = [
+    ("tiny", 256, 256, 8, "f32"), ("tiny", 256, 256, 8, "bf16"), ("tiny", 70, 200, 1, "f32"),
+    ("tiny", 70, 200, 33, "f32"), ("tiny", 33, 70, 5, "bf16"),
+    ("fig1", 200, 448, 64, "bf16"), ("fig1", 200, 448, 63, "bf16"), ("fig1", 64, 2048, 1, "bf16"),
+    ("fc6", 97, 640, 1, "bf16"), ("fc6", 97, 640, 64, "bf16"), ("fc6", 97, 640, 100, "bf16"), ("fc6", 97, 640, 4, "f32"),
+    ("lstm", 130, 3000, 1, "bf16"), ("lstm", 130, 3000, 32, "bf16"), ("lstm", 130, 3000, 40, "f32"),
+    ("large_q1", 320, 1024, 1, "bf16"), ("large_q1", 320, 1024, 8, "bf16"), ("large_q1", 320, 1024, 64, "bf16"),
+    ("large_q1", 320, 1024, 256, "bf16"), ("large_q1", 320, 1024, 130, "bf16"),
+    ("large_q2", 96, 4096, 8, "bf16"), ("large_q2", 96, 4096, 256, "bf16"), ("large_q2", 96, 4096, 16, "f32"),
+]
+
+
+@pytest.mark.parametrize("name,m,n,B,dtype", SMALL_CASES)
+def test_spmm_matches_fp64_oracle(name, m, n, B, dtype):
+    got, want = _run(name, m, n, B, dtype)
+    assert got.shape == want.shape
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL[dtype]
+
+
+FULL_CASES = [("fig1", 64), ("fc6", 1), ("fc6", 64), ("lstm", 1), ("lstm", 32), ("large_q1", 1), ("large_q1", 8),
+              ("large_q1", 64), ("large_q1", 256), ("large_q2", 1), ("large_q2", 8), ("large_q2", 64), ("large_q2", 256)]
+
+
+@pytest.mark.parametrize("name,B", FULL_CASES)
+def test_spmm_full_size_configs(name, B):
+    got, want = _run(name, None, None, B, "bf16")
+    err = rel_fro(got, want)
+    assert err <= TOL["bf16"], err
+    # per-row check on a sample, so a wrong row cannot hide in the norm
+    rows = np.random.default_rng(B).integers(0, got.shape[0], size=64)
+    for r in rows:
+        assert rel_fro(got[r], want[r]) <= 10 * TOL["bf16"]
+
+
+def test_tiny_config_fp32_full():
+    got, want = _run("tiny", None, None, 8, "f32")
+    assert rel_fro(got, want) <= TOL["f32"]
+
+
+def test_odd_leading_dimension_and_unaligned_rows():
+    got, want = _run("fig1", 200, 448, 64, "bf16", ldx_pad=3)     # ldx = 67: the 16-bit load path
+    assert rel_fro(got, want) <= TOL["bf16"]
+    got, want = _run("fig1", 200, 448, 6, "f32", ldx_pad=1)
+    assert rel_fro(got, want) <= TOL["f32"]
+
+
+def test_identity_X_reproduces_decoded_weights():
+    """Y = W I = W: the fused path against the decode path, no oracle involved in the comparison."""
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc = encoded_workload("fc6", 97, 640)
+    L = pack_encoded(enc).to(torch.device("cuda:0"))
+    X = torch.eye(wl.n, dtype=torch.float32, device="cuda:0")
+    Y = xe.spmm(L, X).cpu().numpy()
+    W = xe.decode(L, xe.OUT_F32).cpu().numpy()
+    assert np.allclose(Y, W, rtol=1e-6, atol=1e-9)
+    assert np.allclose(W, decoder.dequantize_f64(enc), rtol=1e-6, atol=0)
+
+
+def test_output_leading_dimension_and_overwrite():
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc = encoded_workload("fig1", 200, 448)
+    L = pack_encoded(enc).to(torch.device("cuda:0"))
+    stored, exact = draw_X(wl.n, 64, "bf16", 99)
+    xg = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    buf = torch.full((200, 80), 3.0, dtype=torch.float32, device="cuda:0")
+    xe.spmm(L, xg, Y=buf[:, :64])
+    got = buf.cpu().numpy()
+    assert rel_fro(got[:, :64], decoder.spmm_f64(enc, exact)) <= TOL["bf16"]
+    assert np.all(got[:, 64:] == 3.0)

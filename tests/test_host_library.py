@@ -1,0 +1,127 @@
+"""CPU-side tests of libxorenc.so: exported symbols, sizes, pack/unpack round trip, content
+checker, argument validation (every check happens before any GPU call)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1905_10138_amd as xe
+from paper_1905_10138_amd import binding
+from helpers import encoded_workload, pack_encoded, paper_format_arrays
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = xe.load_library()
+    text = open(os.path.join(ROOT, "include", "xorenc.h")).read()
+    names = set(re.findall(r"XORENC_API[^;(]*?\b(xorenc_\w+)\s*\(", text))
+    assert {"xorenc_decode", "xorenc_spmm", "xorenc_pack", "xorenc_unpack", "xorenc_get_sizes",
+            "xorenc_check_packed", "xorenc_version", "xorenc_strerror", "xorenc_last_hip_error"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert xe.version() >> 16 == 1
+    assert "align" in xe.strerror(-3)
+
+
+def test_sizes():
+    s = xe.get_sizes(6000, 3000, 24, 3)
+    assert (s["n_pad"], s["m_pad"], s["spr"]) == (3008, 6016, 47)
+    assert s["n_slots"] == 6016 * 47 and s["n_units"] == 188 * 47
+    assert s["enc_bytes"] == 3 * s["n_slots"] * 3 and s["patch_off_words"] == 3 * s["n_units"] + 1
+    for bad in [(0, 8, 8, 1), (8, 0, 8, 1)]:
+        with pytest.raises(xe.XorencError) as e:
+            xe.get_sizes(*bad)
+        assert e.value.code == -1
+    for bad in [(8, 8, 12, 1), (8, 8, 8, 5), (8, 8, 40, 1)]:
+        with pytest.raises(xe.XorencError) as e:
+            xe.get_sizes(*bad)
+        assert e.value.code == -2
+
+
+@pytest.mark.parametrize("name,m,n", [("tiny", 70, 256), ("lstm", 45, 200), ("large_q2", 64, 512), ("fc6", 33, 130)])
+def test_pack_unpack_roundtrip(name, m, n):
+    wl, enc = encoded_workload(name, m, n)
+    w_c, keep, n_patch, d_patch, M_rows = paper_format_arrays(enc)
+    L = pack_encoded(enc)
+    assert xe.check_packed(L) == 0
+    w2, k2, np2, dp2 = xe.unpack(L)
+    assert np.array_equal(w2, w_c) and np.array_equal(k2, keep)
+    assert np.array_equal(np2, n_patch) and np.array_equal(dp2, d_patch)
+    # layout spot checks straight from the documented slot formula
+    spr = wl.n_pad // 64
+    nib = enc.n_in // 8
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        r, s, p = rng.integers(m), rng.integers(spr), rng.integers(enc.q)
+        slot = ((r // 32) * spr + s) * 32 + r % 32
+        assert L.mask[slot] == keep[r * spr + s]
+        got = int.from_bytes(L.enc[(p * L.mask.size + slot) * nib:(p * L.mask.size + slot + 1) * nib].tobytes(), "little")
+        assert got == w_c[p, r * spr + s]
+    assert int(L.patch_off[-1]) == d_patch.size
+    assert np.all(np.diff(L.patch_off.astype(np.int64)) >= 0)
+
+
+def test_pack_rejects_malformed_patch_data():
+    wl, enc = encoded_workload("large_q1", 64, 512)
+    w_c, keep, n_patch, d_patch, M_rows = paper_format_arrays(enc)
+    assert d_patch.size > 2
+    with pytest.raises(xe.XorencError) as e:        # one entry short
+        xe.pack(enc.m, enc.n, enc.n_in, enc.q, w_c, keep, n_patch, d_patch[:-1], enc.alpha, M_rows)
+    assert e.value.code == -5
+    bad = d_patch.copy(); bad[0] = 64
+    with pytest.raises(xe.XorencError):
+        xe.pack(enc.m, enc.n, enc.n_in, enc.q, w_c, keep, n_patch, bad, enc.alpha, M_rows)
+    wbad = w_c.copy(); wbad[0, 0] |= 1 << 8        # bit beyond n_in = 8
+    with pytest.raises(xe.XorencError):
+        xe.pack(enc.m, enc.n, enc.n_in, enc.q, wbad, keep, n_patch, d_patch, enc.alpha, M_rows)
+
+
+def test_check_packed_finds_planted_damage():
+    wl, enc = encoded_workload("large_q1", 64, 512)
+    L = pack_encoded(enc)
+    assert xe.check_packed(L) == 0
+    off = L.patch_off.copy()
+    i = int(np.flatnonzero(np.diff(off.astype(np.int64)) > 0)[0])
+    L.patch_off = off.copy(); L.patch_off[i + 1] = off[i] - 1 if off[i] > 0 else off[i + 2] + 5
+    assert xe.check_packed(L) == -5
+    L.patch_off = off
+    p = L.patch.copy(); p[0] = (p[0] & ~np.uint16(63)) | np.uint16(int(np.flatnonzero(
+        [(int(L.mask[i * 32 + (int(p[0]) >> 6)]) >> b) & 1 == 0 for b in range(64)])[0]))
+    L.patch = p                                      # patch moved onto a pruned position
+    assert xe.check_packed(L) == -5
+
+
+def test_gpu_entry_points_validate_before_touching_the_gpu():
+    lib = xe.load_library()
+    wl, enc = encoded_workload("tiny", 70, 256)
+    L = pack_encoded(enc)
+    st = L.c_struct()                                # host pointers: fine for validation-only calls
+    out = np.zeros(8, np.uint64)
+    assert lib.xorenc_decode(None, 0, out.ctypes.data, 0, None) == -1
+    assert lib.xorenc_decode(ctypes.byref(st), 0, None, 0, None) == -1
+    assert lib.xorenc_decode(ctypes.byref(st), 7, out.ctypes.data, 0, None) == -2
+    assert lib.xorenc_decode(ctypes.byref(st), 1, out.ctypes.data, 10, None) == -1        # ld < n
+    assert lib.xorenc_decode(ctypes.byref(st), 0, out.ctypes.data + 4, 0, None) == -3
+    bad = L.c_struct(); bad.struct_size = 8
+    assert lib.xorenc_decode(ctypes.byref(bad), 0, out.ctypes.data, 0, None) == -1
+    bad = L.c_struct(); bad.n_out = 128
+    assert lib.xorenc_decode(ctypes.byref(bad), 0, out.ctypes.data, 0, None) == -2
+    bad = L.c_struct(); bad.q = 9
+    assert lib.xorenc_spmm(ctypes.byref(bad), out.ctypes.data, 1, 8, 8, out.ctypes.data, 8, None) == -2
+    bad = L.c_struct(); bad.mask = (bad.mask or 0) + 4
+    assert lib.xorenc_spmm(ctypes.byref(bad), out.ctypes.data, 1, 8, 8, out.ctypes.data, 8, None) == -3
+    assert lib.xorenc_spmm(ctypes.byref(st), None, 1, 8, 8, out.ctypes.data, 8, None) == -1
+    assert lib.xorenc_spmm(ctypes.byref(st), out.ctypes.data, 1, 4, 8, out.ctypes.data, 8, None) == -1   # ldx < B
+    assert lib.xorenc_spmm(ctypes.byref(st), out.ctypes.data, 1, 8, 0, out.ctypes.data, 8, None) == -1   # B = 0
+    assert lib.xorenc_spmm(ctypes.byref(st), out.ctypes.data, 5, 8, 8, out.ctypes.data, 8, None) == -2
+    assert lib.xorenc_spmm(ctypes.byref(st), out.ctypes.data + 1, 1, 8, 8, out.ctypes.data, 8, None) == -3
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libxorenc.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load_library()
