@@ -60,7 +60,8 @@ def test_unit_inputs_decode_to_columns_of_M():
     import torch
     import paper_1905_10138_amd as xe
     rng = np.random.default_rng(5)
-    n_in, m, n = 24, 64, 64 * n_in
+    n_in, m = 24, 64
+    n = 64 * n_in
     M = rng.integers(0, 2, size=(64, n_in), dtype=np.uint8)
     spr = n // 64
     w_c = np.tile((np.uint32(1) << np.arange(n_in, dtype=np.uint32)), m)[None]      # slice s of every row: e_s
