@@ -139,6 +139,34 @@ XORENC_API int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, 
 XORENC_API int32_t xorenc_check_packed(const xorenc_layer *layer_with_host_buffers);
 
 /*
+ * Re-arrange a dense 0/1 byte matrix (HOST, row-major m x n, leading dimension ld >= n bytes) into
+ * unit-major 64-bit slice words (HOST uint64[n_slots]): bit j of word slot(r,s) = a[r][64 s + j] != 0;
+ * padding rows and columns are 0.  Used to hand masks and quantised bit-planes to xorenc_encode.
+ */
+XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, const uint8_t *a, int64_t ld, uint64_t *out);
+
+/*
+ * Encoder on the GPU: Algorithm 1 (patch searching) of Section 3.3 for every slice of every plane,
+ * one slice per lane.  Care bits are visited in ascending position; an equation that makes the
+ * system unsolvable is dropped and becomes a patch; free variables of the final system are 0, so
+ * the result is the unique solution the reduced row-echelon form gives.
+ *   M_rows     HOST uint32[64]
+ *   mask       DEV  uint64[n_slots]      care mask, unit-major (the layer's mask buffer itself)
+ *   planes     DEV  uint64[q][n_slots]   quantised bits, unit-major; bits at pruned positions are ignored
+ *   enc_out    DEV  uint8[q][n_slots][n_in/8]
+ *   patch_off_out DEV uint32[q*n_units + 1]
+ *   patch_out  DEV  uint16[patch_capacity]; entries beyond the capacity are not written.  The caller
+ *              must compare patch_off_out[q*n_units] (the true total) with patch_capacity after the
+ *              stream has run, and retry with a larger buffer if it is larger.
+ *   workspace  DEV  uint64[q*n_slots] + uint32[q*n_units] bytes, 8-byte aligned (scratch, contents undefined after)
+ * Three kernels are enqueued on hip_stream; nothing synchronises.
+ */
+XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *M_rows,
+                                 const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
+                                 uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity,
+                                 void *workspace, int64_t workspace_bytes, void *hip_stream);
+
+/*
  * Decode only (Sections 3.1-3.2 + mask + dequantisation).
  *   XORENC_OUT_PLANES: out = DEV uint64[q][m*spr], word p*(m*spr) + r*spr + s = decrypted, patched
  *                      slice with pruned and padding positions forced to 0; ld_out ignored.

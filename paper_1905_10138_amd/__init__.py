@@ -9,10 +9,12 @@ from .binding import (
     XorencError,
     check_packed,
     decode,
+    encode,
     get_sizes,
     library_path,
     load_library,
     pack,
+    pack_bits,
     spmm,
     strerror,
     unpack,
@@ -20,6 +22,6 @@ from .binding import (
 )
 
 __all__ = [
-    "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode",
+    "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode", "encode", "pack_bits",
     "get_sizes", "library_path", "load_library", "pack", "spmm", "strerror", "unpack", "version",
 ]

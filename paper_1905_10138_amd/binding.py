@@ -70,6 +70,10 @@ def load_library():
     lib.xorenc_unpack.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.xorenc_check_packed.restype = i32
     lib.xorenc_check_packed.argtypes = [ctypes.POINTER(_Layer)]
+    lib.xorenc_pack_bits.restype = i32
+    lib.xorenc_pack_bits.argtypes = [i32, i32, vp, i64, vp]
+    lib.xorenc_encode.restype = i32
+    lib.xorenc_encode.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
     lib.xorenc_decode.restype = i32
     lib.xorenc_decode.argtypes = [ctypes.POINTER(_Layer), i32, vp, i64, vp]
     lib.xorenc_spmm.restype = i32
@@ -145,6 +149,13 @@ class PackedLayer:
                            mv(self.enc), mv(self.mask, np.int64), mv(self.patch_off, np.int32),
                            mv(self.patch, np.int16), mv(self.alpha))
 
+    def to_host(self) -> "PackedLayer":
+        def mv(t, dt):
+            return t.detach().cpu().contiguous().numpy().view(dt)
+        return PackedLayer(self.m, self.n, self.n_in, self.q, self.M_rows, mv(self.enc, np.uint8),
+                           mv(self.mask, np.uint64), mv(self.patch_off, np.uint32), mv(self.patch, np.uint16),
+                           mv(self.alpha, np.float32))
+
     def compressed_bytes(self) -> int:
         """Bytes of every device buffer a kernel reads for this layer."""
         def nb(b):
@@ -189,6 +200,46 @@ def unpack(layer: PackedLayer):
                              _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
                              _np_ptr(d_patch) if d_patch.size else None), "xorenc_unpack")
     return w_c, keep, n_patch, d_patch
+
+
+def pack_bits(a: np.ndarray) -> np.ndarray:
+    """xorenc_pack_bits: dense 0/1 matrix (m, n) -> unit-major uint64 slice words (host)."""
+    a = np.ascontiguousarray(a).view(np.uint8) if a.dtype == np.bool_ else _as(a, np.uint8)
+    m, n = a.shape
+    spr, nrb = (n + 63) // 64, (m + 31) // 32
+    out = np.empty(nrb * 32 * spr, np.uint64)
+    _check(load_library().xorenc_pack_bits(m, n, _np_ptr(a), a.strides[0], _np_ptr(out)), "xorenc_pack_bits")
+    return out
+
+
+def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[int] = None) -> PackedLayer:
+    """xorenc_encode on the current stream.  mask: int64 GPU tensor [n_slots] (unit-major words),
+    planes: int64 GPU tensor [q, n_slots], alpha: float32 GPU tensor [q, m].  Returns a device
+    PackedLayer that shares `mask` and `alpha`.  Synchronises once to read the patch total (the
+    C call itself does not) and retries with a larger patch buffer if the first was too small."""
+    import torch
+    lib = load_library()
+    sz = get_sizes(m, n, n_in, q)
+    dev = mask.device
+    M_rows = _as(M_rows, np.uint32).reshape(64)
+    if mask.numel() != sz["n_slots"] or planes.numel() != q * sz["n_slots"]:
+        raise ValueError("mask/planes do not have n_slots words per plane")
+    enc = torch.empty(sz["enc_bytes"], dtype=torch.uint8, device=dev)
+    patch_off = torch.empty(sz["patch_off_words"], dtype=torch.int32, device=dev)
+    ws_bytes = q * sz["n_slots"] * 8 + q * sz["n_units"] * 4
+    ws = torch.empty((ws_bytes + 7) // 8, dtype=torch.int64, device=dev)
+    cap = int(patch_capacity) if patch_capacity is not None else max(1024, q * sz["n_slots"] // 8)
+    while True:
+        patch = torch.empty(cap, dtype=torch.int16, device=dev)
+        _check(lib.xorenc_encode(m, n, n_in, q, _np_ptr(M_rows), ctypes.c_void_p(mask.data_ptr()),
+                                 ctypes.c_void_p(planes.data_ptr()), ctypes.c_void_p(enc.data_ptr()),
+                                 ctypes.c_void_p(patch_off.data_ptr()), ctypes.c_void_p(patch.data_ptr()), cap,
+                                 ctypes.c_void_p(ws.data_ptr()), ws.numel() * 8, _stream_ptr()), "xorenc_encode")
+        total = int(patch_off[-1].item())
+        if total <= cap:
+            break
+        cap = total
+    return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch[:total], alpha)
 
 
 def check_packed(layer: PackedLayer) -> int:

@@ -1,0 +1,178 @@
+// GPU encoder: Algorithm 1 (patch searching, Section 3.3 of arXiv 1905.10138) for every slice,
+// one slice per lane.
+//
+// Per slice the accepted equations are kept in row-echelon form in LDS: basis[j] is the accepted
+// (reduced) row whose lowest set coefficient is column j.  A new care-bit equation
+// (M_i | w_i) is reduced against the basis in ascending pivot order; if its coefficients vanish
+// it is either redundant (right-hand side 0) or contradicts the accepted ones (right-hand side
+// 1): then it is dropped and position i becomes a patch.  Otherwise it joins the basis.  After
+// the last care bit, back-substitution with every free variable 0 gives w^c, which is the
+// solution the reduced row-echelon form of the accepted rows yields.
+#include <hip/hip_runtime.h>
+
+#include "xorenc_internal.h"
+
+namespace {
+
+constexpr int ENC_THREADS = 256;
+
+struct EncParams {
+  const uint64_t *mask;
+  const uint64_t *planes;
+  uint8_t *enc;
+  uint64_t *pbits;      // [q][n_slots] patch bitmaps (workspace)
+  uint32_t *counts;     // [q*n_units] patches per unit (workspace)
+  int64_t n_slots;
+  int32_t n_units, n_in, nib, q;
+  uint32_t M_rows[64];
+};
+
+__global__ __launch_bounds__(ENC_THREADS) void encode_slices_kernel(EncParams P) {
+  __shared__ uint32_t basis[XORENC_MAX_N_IN][ENC_THREADS];
+  const int tid = threadIdx.x;
+  const int64_t gid = (int64_t)blockIdx.x * ENC_THREADS + tid;  // (plane, slot) flattened
+  const int64_t total = (int64_t)P.q * P.n_slots;
+  const bool valid = gid < total;
+  const int64_t slot = valid ? gid % P.n_slots : 0;
+  const int p = valid ? (int)(gid / P.n_slots) : 0;
+
+  uint64_t care = valid ? P.mask[slot] : 0ull;
+  const uint64_t bits = valid ? P.planes[(int64_t)p * P.n_slots + slot] : 0ull;
+  uint32_t have = 0;     // bit j: a basis row with pivot j exists
+  uint32_t rhsbits = 0;  // bit j: right-hand side of that row
+  uint64_t patches = 0;
+
+  while (care) {
+    const int i = __builtin_ctzll(care);
+    care &= care - 1;
+    uint32_t row = P.M_rows[i];
+    uint32_t rhs = (uint32_t)((bits >> i) & 1);
+    uint32_t t = row & have;
+    while (t) {  // reduce, ascending pivots
+      const int j = __builtin_ctz(t);
+      row ^= basis[j][tid];
+      rhs ^= (rhsbits >> j) & 1u;
+      t = row & have & ~((2u << j) - 1u);
+    }
+    if (row == 0) {
+      if (rhs) patches |= 1ull << i;  // 0 ... 0 | 1: unsolvable, the equation is dropped
+      continue;
+    }
+    const int piv = __builtin_ctz(row);
+    basis[piv][tid] = row;
+    have |= 1u << piv;
+    rhsbits |= rhs << piv;
+  }
+  // back-substitution, free variables = 0, highest pivot first
+  uint32_t x = 0;
+  uint32_t t = have;
+  while (t) {
+    const int j = 31 - __builtin_clz(t);
+    t &= ~(1u << j);
+    const uint32_t others = basis[j][tid] & x;  // pivots above j already solved; free ones are 0
+    const uint32_t v = ((rhsbits >> j) & 1u) ^ (__builtin_popcount(others) & 1u);
+    x |= v << j;
+  }
+  if (valid) {
+    uint8_t *dst = P.enc + ((int64_t)p * P.n_slots + slot) * P.nib;
+    for (int b = 0; b < P.nib; ++b) dst[b] = (uint8_t)(x >> (8 * b));
+    P.pbits[gid] = patches;
+  }
+  // patches per unit = sum over the 32 lanes that share it (n_slots is a multiple of 32)
+  int cnt = __builtin_popcountll(patches);
+#pragma unroll
+  for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_down(cnt, o, 32);
+  if (valid && (tid & 31) == 0) P.counts[gid >> 5] = (uint32_t)cnt;
+}
+
+// exclusive scan of counts[0..n) into off[0..n], one workgroup
+__global__ __launch_bounds__(1024) void scan_counts_kernel(const uint32_t *counts, uint32_t *off, int n) {
+  __shared__ uint32_t part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int a = min(n, tid * per), e = min(n, a + per);
+  uint32_t s = 0;
+  for (int i = a; i < e; ++i) s += counts[i];
+  part[tid] = s;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {
+    const uint32_t v = (tid >= d) ? part[tid - d] : 0u;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - s;  // exclusive prefix of this thread's chunk
+  for (int i = a; i < e; ++i) {
+    off[i] = run;
+    run += counts[i];
+  }
+  if (tid == 1023) off[n] = part[1023];
+}
+
+__global__ __launch_bounds__(ENC_THREADS) void emit_patches_kernel(const uint64_t *pbits, const uint32_t *off,
+                                                                  uint16_t *patch, int64_t capacity,
+                                                                  int64_t total_slots) {
+  const int64_t gid = (int64_t)blockIdx.x * ENC_THREADS + threadIdx.x;
+  const bool valid = gid < total_slots;
+  uint64_t w = valid ? pbits[gid] : 0ull;
+  const int cnt = __builtin_popcountll(w);
+  // exclusive prefix of cnt inside the 32-lane unit
+  int incl = cnt;
+#pragma unroll
+  for (int o = 1; o < 32; o <<= 1) {
+    const int v = __shfl_up(incl, o, 32);
+    if ((threadIdx.x & 31) >= o) incl += v;
+  }
+  if (!valid || !w) return;
+  int64_t pos = (int64_t)off[gid >> 5] + (incl - cnt);
+  const uint32_t rr = (uint32_t)(gid & 31);
+  while (w) {
+    const int bit = __builtin_ctzll(w);
+    w &= w - 1;
+    if (pos < capacity) patch[pos] = (uint16_t)((rr << 6) | bit);
+    ++pos;
+  }
+}
+
+}  // namespace
+
+extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *M_rows,
+                                 const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
+                                 uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity,
+                                 void *workspace, int64_t workspace_bytes, void *hip_stream) {
+  xorenc_sizes sz;
+  const int32_t rc = xorenc_get_sizes(m, n, n_in, q, &sz);
+  if (rc != XORENC_OK) return rc;
+  if (!M_rows || !mask || !planes || !enc_out || !patch_off_out || !workspace || patch_capacity < 0)
+    return XORENC_EINVAL;
+  if (patch_capacity > 0 && !patch_out) return XORENC_EINVAL;
+  const int64_t total = (int64_t)q * sz.n_slots;
+  const int64_t n_counts = (int64_t)q * sz.n_units;
+  if (workspace_bytes < total * 8 + n_counts * 4) return XORENC_EINVAL;
+  if (n_counts > (int64_t)1 << 30) return XORENC_EUNSUPPORTED;
+  if (((uintptr_t)mask & 7) || ((uintptr_t)planes & 7) || ((uintptr_t)workspace & 7) ||
+      ((uintptr_t)patch_off_out & 3) || ((uintptr_t)patch_out & 1))
+    return XORENC_EALIGN;
+  EncParams P;
+  P.mask = mask;
+  P.planes = planes;
+  P.enc = enc_out;
+  P.pbits = static_cast<uint64_t *>(workspace);
+  P.counts = reinterpret_cast<uint32_t *>(static_cast<uint64_t *>(workspace) + total);
+  P.n_slots = sz.n_slots;
+  P.n_units = (int32_t)sz.n_units;
+  P.n_in = n_in;
+  P.nib = n_in / 8;
+  P.q = q;
+  for (int i = 0; i < 64; ++i) {
+    if (n_in < 32 && (M_rows[i] >> n_in)) return XORENC_EINVAL;
+    P.M_rows[i] = M_rows[i];
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const unsigned blocks = (unsigned)((total + ENC_THREADS - 1) / ENC_THREADS);
+  hipLaunchKernelGGL(encode_slices_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, P);
+  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, P.counts, patch_off_out, (int)n_counts);
+  hipLaunchKernelGGL(emit_patches_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, P.pbits, patch_off_out, patch_out,
+                     patch_capacity, total);
+  return xorenc_internal_check_launch();
+}

@@ -142,6 +142,22 @@ int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint8
   return XORENC_OK;
 }
 
+int32_t xorenc_pack_bits(int32_t m, int32_t n, const uint8_t *a, int64_t ld, uint64_t *out) {
+  if (!a || !out || m <= 0 || n <= 0 || ld < n) return XORENC_EINVAL;
+  const int64_t spr = ((int64_t)n + 63) / 64, nrb = ((int64_t)m + 31) / 32;
+  std::memset(out, 0, (size_t)(nrb * 32 * spr) * sizeof(uint64_t));
+  for (int64_t r = 0; r < m; ++r) {
+    const uint8_t *row = a + r * ld;
+    for (int64_t s = 0; s < spr; ++s) {
+      uint64_t w = 0;
+      const int lim = (int)((n - s * 64) < 64 ? (n - s * 64) : 64);
+      for (int j = 0; j < lim; ++j) w |= (uint64_t)(row[s * 64 + j] != 0) << j;
+      out[((r / 32) * spr + s) * 32 + (r % 32)] = w;
+    }
+  }
+  return XORENC_OK;
+}
+
 int32_t xorenc_check_packed(const xorenc_layer *L) {
   if (!L || L->struct_size != sizeof(xorenc_layer)) return XORENC_EINVAL;
   if (L->n_out != XORENC_N_OUT) return XORENC_EUNSUPPORTED;

@@ -7,4 +7,7 @@
 #define XORENC_MAX_Q 4
 #define XORENC_MAX_N_IN 32
 
+/* hipGetLastError() -> XORENC_OK / XORENC_EHIP; remembers the hipError_t per thread. */
+int32_t xorenc_internal_check_launch(void);
+
 #endif

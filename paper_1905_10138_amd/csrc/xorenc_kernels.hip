@@ -17,9 +17,18 @@
 
 #include "xorenc_internal.h"
 
-namespace {
+static thread_local int32_t g_last_hip_error = 0;
 
-thread_local int32_t g_last_hip_error = 0;
+int32_t xorenc_internal_check_launch(void) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_last_hip_error = (int32_t)e;
+    return XORENC_EHIP;
+  }
+  return XORENC_OK;
+}
+
+namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -436,14 +445,7 @@ int32_t fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   return XORENC_OK;
 }
 
-int32_t check_launch() {
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    g_last_hip_error = (int32_t)e;
-    return XORENC_EHIP;
-  }
-  return XORENC_OK;
-}
+int32_t check_launch() { return xorenc_internal_check_launch(); }
 
 template <int NCB, int Q, int RB, bool XF32>
 int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, int x_fast,
