@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused decode + W X path on one MI355X.
+
+A step is one xorenc_spmm call: the whole hot path (stream-in, GF(2) decode, patch flips, mask,
+dequantise, contraction) over one batch X of the workload.  Inputs are synthetic (seeded, see
+synth_inputs), encoded on the GPU by xorenc_encode before timing, and resident in HBM.  To keep
+the timed reads cold (the layers are far smaller than the 256 MB last-level cache) the steps walk
+round-robin over R replicas of the compressed layer, X and Y with R * bytes >= 1 GiB.  Steps are
+issued back to back on one stream from a captured HIP graph so that host launch cost does not
+pace the GPU.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="large_q1", help="one of synth_inputs.CONFIGS")
+    ap.add_argument("--batch", type=int, default=64, help="columns of X (B)")
+    ap.add_argument("--sweep", default="1,8,64,256", help="other batch sizes reported under 'sweep' ('' = none)")
+    ap.add_argument("--sweep-steps", type=int, default=400)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of from a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of W in the CPU-oracle sample (0 = auto)")
+    ap.add_argument("--replica-bytes", type=float, default=float(1 << 30))
+    ap.add_argument("--decode-only", action="store_true", help="also time xorenc_decode (planes) on the workload")
+    return ap.parse_args()
+
+
+def build_layer(wl, xe, torch, dev):
+    """Encode the workload on the GPU (xorenc_encode) and return the device layer."""
+    mask = torch.from_numpy(xe.pack_bits(wl.keep[:, :wl.n]).view(np.int64)).to(dev)
+    planes = torch.from_numpy(
+        np.stack([xe.pack_bits(wl.planes[p][:, :wl.n]) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
+    alpha = torch.from_numpy(wl.alpha).to(dev)
+    M_rows = (wl.M.astype(np.uint64) << np.arange(wl.cfg.n_in, dtype=np.uint64)).sum(axis=1).astype(np.uint32)
+    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha)
+
+
+def clone_layer(L, xe):
+    return xe.PackedLayer(L.m, L.n, L.n_in, L.q, L.M_rows, L.enc.clone(), L.mask.clone(), L.patch_off.clone(),
+                          L.patch.clone(), L.alpha.clone())
+
+
+class SpmmRunner:
+    """Pre-marshalled xorenc_spmm calls over R replicas (no Python work per step beyond the ctypes call)."""
+
+    def __init__(self, xe, torch, layer, x_dev, B, replica_bytes):
+        self.torch = torch
+        self.lib = xe.load_library()
+        self.B = B
+        xbytes = x_dev.numel() * x_dev.element_size()
+        ybytes = layer.m * B * 4
+        self.comp_bytes = layer.compressed_bytes()
+        self.step_bytes = self.comp_bytes + xbytes + ybytes
+        R = int(min(256, max(2, np.ceil(replica_bytes / self.step_bytes))))
+        self.layers = [layer] + [clone_layer(layer, xe) for _ in range(R - 1)]
+        self.xs = [x_dev] + [x_dev.clone() for _ in range(R - 1)]
+        self.ys = [torch.empty((layer.m, B), dtype=torch.float32, device=x_dev.device) for _ in range(R)]
+        self.structs = [l.c_struct() for l in self.layers]
+        xd = 0 if x_dev.dtype == torch.float32 else 1
+        self.calls = []
+        for st, x, y in zip(self.structs, self.xs, self.ys):
+            self.calls.append((ctypes.byref(st), ctypes.c_void_p(x.data_ptr()), xd, x.stride(0), B,
+                               ctypes.c_void_p(y.data_ptr()), y.stride(0)))
+        self.R = R
+        self.pos = 0
+        self.graph = None
+
+    def launch(self, count):
+        fn = self.lib.xorenc_spmm
+        stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+        for _ in range(count):
+            rc = fn(*self.calls[self.pos], stream)
+            if rc != 0:
+                raise RuntimeError(f"xorenc_spmm failed with status {rc}")
+            self.pos = (self.pos + 1) % self.R
+
+    def capture(self):
+        """Capture one rotation (R steps) into a HIP graph."""
+        torch = self.torch
+        self.pos = 0
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            self.launch(self.R)  # warm the code objects before capture
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            self.launch(self.R)
+        self.graph = g
+
+    def run(self, steps):
+        """Issue exactly `steps` steps (graph replays of R steps + an eager remainder)."""
+        if self.graph is not None:
+            for _ in range(steps // self.R):
+                self.graph.replay()
+            self.pos = 0
+            self.launch(steps % self.R)
+        else:
+            self.launch(steps)
+
+    def time(self, steps, warmup):
+        torch = self.torch
+        self.run(warmup)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        self.run(steps)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, e0.elapsed_time(e1) * 1e-3
+
+
+def roofline_entry(flops, comp_bytes, total_bytes, sec_per_launch, B):
+    if B >= 32:
+        ach = flops / sec_per_launch / 1e12
+        return {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    ach = comp_bytes / sec_per_launch / 1e9
+    return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": None, "total_bytes_gbs": total_bytes / sec_per_launch / 1e9}
+
+
+def cpu_baseline(wl, B, x_exact, y_gpu_rows, rows):
+    """Time the CPU oracle (decode + fp64 product) on the first `rows` rows of the same workload."""
+    from oracle import decoder, encoder
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    enc = encoder.encode(wl.keep[:rows], wl.planes[:, :rows], wl.alpha[:, :rows], wl.M, wl.n)  # not timed (offline step)
+    times = []
+    y = None
+    for _ in range(3):
+        t0 = time.perf_counter()
+        y = decoder.spmm_f64(enc, x_exact)
+        times.append(time.perf_counter() - t0)
+    t = float(np.median(times))
+    err = float(np.linalg.norm(y_gpu_rows - y) / max(np.linalg.norm(y), 1e-300))
+    flops = 2.0 * rows * wl.n * B
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {rows} of {wl.m} rows of the same W, X and B; median of 3; oracle decode + fp64 W X",
+            "seconds": t, "gpu_vs_oracle_rel_fro": err}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_1905_10138_amd as xe
+    from synth_inputs import CONFIGS, make_workload
+
+    xe.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.workload]
+    t_gen = time.perf_counter()
+    wl = make_workload(cfg)
+    layer = build_layer(wl, xe, torch, dev)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    def x_for(B):
+        stored, exact = wl.X(B)
+        if cfg.x_dtype == "bf16":
+            return torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev), exact
+        return torch.from_numpy(stored).to(dev), exact
+
+    def measure(B, steps, warmup):
+        xg, xexact = x_for(B)
+        runner = SpmmRunner(xe, torch, layer, xg, B, args.replica_bytes)
+        if not args.no_graph:
+            runner.capture()
+        wall, ev = runner.time(steps, warmup)
+        flops = 2.0 * wl.m * wl.n * B
+        res = {"B": B, "ms_per_step": wall * 1e3 / steps, "us_per_launch_events": ev * 1e6 / steps,
+               "tflops": flops * steps / wall / 1e12, "compressed_gbs": runner.comp_bytes * steps / wall / 1e9,
+               "replicas": runner.R, "step_bytes": runner.step_bytes, "compressed_bytes": runner.comp_bytes,
+               "roofline": roofline_entry(flops, runner.comp_bytes, runner.step_bytes, ev / steps, B)}
+        return res, runner, xexact
+
+    main_res, runner, xexact = measure(args.batch, args.steps, args.warmup)
+    y0 = runner.ys[0].cpu().numpy()
+
+    sweep = []
+    for tok in [t for t in args.sweep.split(",") if t.strip()]:
+        B = int(tok)
+        if B == args.batch or B not in cfg.batches:
+            continue
+        r, _, _ = measure(B, args.sweep_steps, max(10, args.sweep_steps // 10))
+        sweep.append(r)
+
+    extra = {}
+    if args.decode_only:
+        out = xe.decode(layer, xe.OUT_PLANES)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            xe.decode(layer, xe.OUT_PLANES, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 200
+        extra["decode_planes_us"] = us
+        extra["decode_planes_gbs"] = (layer.compressed_bytes() + out.numel() * 8) / (us * 1e-6) / 1e9
+
+    out = {
+        "metric": "fused decode+SpMM TFLOP/s & compressed-HBM GB/s (% roofline) at 1 MI355X",
+        "value": main_res["tflops"], "unit": "TFLOP/s (dense-equivalent 2*m*n*B per step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.x_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in={cfg.n_in} n_out=64, "
+                               f"X {cfg.n}x{args.batch} {cfg.x_dtype}",
+                   "B": args.batch, "replicas": main_res["replicas"], "graph": not args.no_graph,
+                   "patches": int(layer.patch.numel()), "compressed_bytes": main_res["compressed_bytes"],
+                   "setup_seconds": t_gen},
+        "compressed_hbm_gbs": main_res["compressed_gbs"],
+        "us_per_launch": main_res["us_per_launch_events"],
+        "roofline": main_res["roofline"],
+        "sweep": sweep,
+    }
+    out.update(extra)
+    if not args.no_cpu_baseline:
+        rows = args.cpu_rows or min(wl.m, 4096)
+        out["cpu_baseline"] = cpu_baseline(wl, args.batch, xexact, y0[:rows].astype(np.float64), rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

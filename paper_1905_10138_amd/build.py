@@ -7,7 +7,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libxorenc.so")
-SOURCES = ["xorenc_host.cpp", "xorenc_kernels.hip", "xorenc_encode.hip"]
+SOURCES = ["xorenc_host.cpp", "xorenc_decode.hip", "xorenc_spmm.hip", "xorenc_encode.hip"]
 
 
 def hipcc_path() -> str:

@@ -1,0 +1,59 @@
+// Device-side structures and helpers shared by the xorenc kernels (arXiv 1905.10138).
+#ifndef XORENC_DEVICE_H
+#define XORENC_DEVICE_H
+
+#include <hip/hip_runtime.h>
+
+#include "xorenc_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct DevLayer {
+  const uint8_t *enc;
+  const uint32_t *mask32;  // the uint64 mask words seen as pairs of 32-bit halves
+  const uint32_t *patch_off;
+  const uint16_t *patch;
+  const float *alpha;
+  int32_t m, n, spr, nrb, n_units, nib, q;
+  int64_t n_slots;
+  uint32_t Mcol_lo[XORENC_MAX_N_IN];  // column j of M, rows 0..31
+  uint32_t Mcol_hi[XORENC_MAX_N_IN];  // column j of M, rows 32..63
+};
+
+
+// T_b[v] for b < nib, v < 256; entry (b*256+v) holds {low 32 rows, high 32 rows}.
+static __device__ inline void build_xor_tables(uint32_t *lut, const DevLayer &L) {
+  for (int idx = threadIdx.x; idx < L.nib * 256; idx += blockDim.x) {
+    const int b = idx >> 8, v = idx & 255;
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if ((v >> t) & 1) {
+        lo ^= L.Mcol_lo[8 * b + t];
+        hi ^= L.Mcol_hi[8 * b + t];
+      }
+    lut[2 * idx] = lo;
+    lut[2 * idx + 1] = hi;
+  }
+}
+
+static __device__ inline uint32_t load_enc(const uint8_t *p, int nib) {
+  switch (nib) {
+    case 1: return p[0];
+    case 2: return *reinterpret_cast<const uint16_t *>(p);
+    case 3: return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16);
+    default: return *reinterpret_cast<const uint32_t *>(p);
+  }
+}
+
+static __device__ inline uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Validates a caller's layer descriptor (host) and fills the kernel-argument form of it.
+int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D);
+
+#endif
