@@ -224,7 +224,7 @@ def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[
     M_rows = _as(M_rows, np.uint32).reshape(64)
     if mask.numel() != sz["n_slots"] or planes.numel() != q * sz["n_slots"]:
         raise ValueError("mask/planes do not have n_slots words per plane")
-    enc = torch.empty(sz["enc_bytes"], dtype=torch.uint8, device=dev)
+    enc = torch.zeros(sz["enc_bytes"], dtype=torch.uint8, device=dev)
     patch_off = torch.empty(sz["patch_off_words"], dtype=torch.int32, device=dev)
     ws_bytes = q * sz["n_slots"] * 8 + q * sz["n_units"] * 4
     ws = torch.empty((ws_bytes + 7) // 8, dtype=torch.int64, device=dev)

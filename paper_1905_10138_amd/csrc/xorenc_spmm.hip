@@ -39,10 +39,10 @@ __device__ inline s16x4 lds_read_tr16(const uint8_t *p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
 }
 
-template <int NCB, int Q, int RB, bool XF32, int NW>
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST>
 __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
-                                                      int use_atomic, int x_fast) {
+                                                      int use_atomic) {
   constexpr int CW = 32 * NCB;             // bf16 columns held in LDS per X row
   constexpr int RSB = CW * 2 + 16;         // LDS row stride in bytes (16 bytes of padding)
   constexpr int XBUF = 64 * RSB;           // one wave's buffer: the 64 X rows of a slice
@@ -83,55 +83,72 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const int s_begin = blockIdx.z * slices_per_split;
   const int s_end = min(L.spr, s_begin + slices_per_split);
 
-  // ---- X loader: one slice = 64 rows x NR columns; chunk i of this lane is (xrow[i], xch[i]).
-  // fast path: lanes tile (row, chunk) pairs; slow path: lane = row and chunks are walked one by one.
+  // ---- this wave's contiguous slice range [w0, w1) inside the workgroup's [s_begin, s_end)
+  const int per_wave = (s_end - s_begin + NW - 1) / NW;
+  const int w0 = min(s_end, s_begin + wave * per_wave);
+  const int w1 = min(s_end, w0 + per_wave);
+  const int cnt = w1 - w0;
+
+  // All global addresses below are (uniform 64-bit base) + (32-bit per-lane offset fixed for the
+  // whole kernel), so the loop spends scalar, not vector, instructions on addressing.
+
+  // ---- X loader.  One slice = 64 rows of X.  Chunk = 16 bytes of a row (8 bf16 / 4 fp32 columns).
+  // XFAST: chunk i of a lane is (row i*(64/NCH) + lane/NCH, chunk lane%NCH), 16-byte loads.
+  // otherwise: lane = row, chunk i is walked element by element (any B, ldx, alignment).
+  // Chunks that lie beyond column B are redirected to chunk 0 (in bounds); what they put into the
+  // padded X columns only reaches output columns that are never stored.
+  constexpr int RPI = 64 / NCH;  // rows covered by one load instruction of the wave (XFAST)
+  constexpr int EPC = XF32 ? 4 : 8;   // X elements per chunk
+  constexpr int ESZ = XF32 ? 4 : 2;   // bytes per X element
   uint4 xr[NCH];
-  auto chunk_row = [&](int i) { return x_fast ? (i * 64 + lane) / NCH : lane; };
-  auto chunk_col = [&](int i) { return x_fast ? (i * 64 + lane) % NCH : i; };
+  // Raw buffer descriptor over the part of X this workgroup may touch: loads beyond the last
+  // row come back as zero from the hardware range check (rows of the padded last slice).
+  const int64_t row_bytes = ldx * ESZ;
+  const uint32_t x_extent = (uint32_t)((int64_t)(L.n - 1) * row_bytes + (int64_t)(B - col0) * ESZ);
+  const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t *>(static_cast<const uint8_t *>(Xv) + (int64_t)col0 * ESZ), 0, x_extent, 0x00020000);
+  const int xrow = XFAST ? lane / NCH : lane;
+  const int xch = XFAST ? lane % NCH : 0;
+  const uint32_t x_lane_off = (uint32_t)(xrow * row_bytes) + ((col0 + xch * EPC < B) ? xch * 16 : 0);
+  const uint32_t x_lds_off = XFAST ? (uint32_t)(xrow * RSB + xch * 16) : (uint32_t)(lane * RSB);
   auto load_x = [&](int s) {
+    const uint32_t sbase = (uint32_t)(s * 64 * row_bytes);  // uniform
+    if constexpr (XFAST) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int row = chunk_row(i), ch = chunk_col(i);
-      const int k = s * 64 + row;
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if constexpr (!XF32) {
-        const uint16_t *X = static_cast<const uint16_t *>(Xv);
-        const int col = col0 + 8 * ch;
-        if (k < L.n && col < B) {
-          const uint16_t *src = X + (int64_t)k * ldx + col;
-          if (x_fast) {
-            v = *reinterpret_cast<const uint4 *>(src);
-          } else {
-            uint32_t h[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = (col + e < B) ? src[e] : 0u;
-            v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-          }
-        }
-      } else {
-        const float *X = static_cast<const float *>(Xv);
-        const int col = col0 + 4 * ch;
-        if (k < L.n && col < B) {
-          const float *src = X + (int64_t)k * ldx + col;
-          if (x_fast) {
-            v = *reinterpret_cast<const uint4 *>(src);
-          } else {
-            v.x = __float_as_uint(src[0]);
-            v.y = (col + 1 < B) ? __float_as_uint(src[1]) : 0u;
-            v.z = (col + 2 < B) ? __float_as_uint(src[2]) : 0u;
-            v.w = (col + 3 < B) ? __float_as_uint(src[3]) : 0u;
-          }
-        }
+      for (int i = 0; i < NCH; ++i) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, x_lane_off, sbase + (uint32_t)(i * RPI * row_bytes), 0);
+        xr[i] = make_uint4(v[0], v[1], v[2], v[3]);
       }
-      xr[i] = v;
+    } else {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        uint32_t h[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+          h[e] = 0u;
+          if (col0 + i * EPC + e < B) {  // uniform
+            const uint32_t so = sbase + (uint32_t)((i * EPC + e) * ESZ);
+            if constexpr (XF32)
+              h[e] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, x_lane_off, so, 0);
+            else
+              h[e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(xrsrc, x_lane_off, so, 0);
+          }
+        }
+        if constexpr (XF32)
+          xr[i] = make_uint4(h[0], h[1], h[2], h[3]);
+        else
+          xr[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+      }
     }
   };
   auto store_x = [&]() {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      const int row = chunk_row(i), ch = chunk_col(i);
+      // XFAST: row advances by RPI per i, chunk fixed; otherwise row fixed, chunk = i
+      const int ch = XFAST ? xch : i;
+      uint8_t *dst_row = xbuf + x_lds_off + (XFAST ? i * RPI * RSB : 0);
       if constexpr (!XF32) {
-        *reinterpret_cast<uint4 *>(xbuf + row * RSB + ch * 16) = xr[i];
+        *reinterpret_cast<uint4 *>(dst_row + (XFAST ? 0 : i * 16)) = xr[i];
       } else {
         // exact split of each fp32 value into three bf16 terms: hi + mid + lo
         const uint32_t f[4] = {xr[i].x, xr[i].y, xr[i].z, xr[i].w};
@@ -147,21 +164,16 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
           part[1][e] = h1;
           part[2][e] = f32_to_bf16_rne(r2);
         }
+        // real column 4*ch+e of the tile -> LDS column (3*(c/32) + part)*32 + c%32; NR = 32 here
+        uint8_t *row_base = XFAST ? dst_row - xch * 16 : dst_row;
 #pragma unroll
         for (int pt = 0; pt < 3; ++pt) {
-          const int cb = 3 * (ch >> 3) + pt;  // 8 chunks of 4 floats per 32 real columns
-          uint2 w2 = make_uint2(part[pt][0] | (part[pt][1] << 16), part[pt][2] | (part[pt][3] << 16));
-          *reinterpret_cast<uint2 *>(xbuf + row * RSB + (cb * 32 + 4 * (ch & 7)) * 2) = w2;
+          const uint2 w2 = make_uint2(part[pt][0] | (part[pt][1] << 16), part[pt][2] | (part[pt][3] << 16));
+          *reinterpret_cast<uint2 *>(row_base + (pt * 32 + 4 * ch) * 2) = w2;
         }
       }
     }
   };
-
-  // ---- this wave's contiguous slice range [w0, w1) inside the workgroup's [s_begin, s_end)
-  const int per_wave = (s_end - s_begin + NW - 1) / NW;
-  const int w0 = min(s_end, s_begin + wave * per_wave);
-  const int w1 = min(s_end, w0 + per_wave);
-  const int cnt = w1 - w0;
 
   // ---- patch lists of the whole range, fetched once: lane i of offv holds the offset of unit i
   // of the range, lane j of entv the j-th entry.  Ranges with more than 63 units or more than 64
@@ -176,8 +188,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       offv[rb][p] = 0u;
       entv[rb][p] = 0u;
       if (rbg < L.nrb && pre_ok && cnt > 0) {
-        const int64_t u0 = (int64_t)p * L.n_units + (int64_t)rbg * L.spr + w0;
-        if (lane <= cnt) offv[rb][p] = L.patch_off[u0 + lane];
+        const uint32_t *po = L.patch_off + ((int64_t)p * L.n_units + (int64_t)rbg * L.spr + w0);
+        if (lane <= cnt) offv[rb][p] = po[lane];
       }
     }
   }
@@ -187,7 +199,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     for (int p = 0; p < Q; ++p) {
       const uint32_t base = __builtin_amdgcn_readlane(offv[rb][p], 0);
       const uint32_t total = __builtin_amdgcn_readlane(offv[rb][p], pre_ok ? cnt : 0) - base;
-      if ((uint32_t)lane < total) entv[rb][p] = L.patch[base + lane];
+      if ((uint32_t)lane < total) entv[rb][p] = (L.patch + base)[lane];
     }
 
   // ---- compressed words of one slice for this lane
@@ -195,6 +207,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     uint32_t mw[RB];
     uint32_t x[RB][Q];
   };
+  const uint32_t m_lane_off = (uint32_t)(rl * 8 + g * 4);
+  const uint32_t e_lane_off = (uint32_t)(rl * L.nib);
   auto load_comp = [&](int s, Comp &c) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -203,29 +217,39 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
       for (int p = 0; p < Q; ++p) c.x[rb][p] = 0u;
       if (rbg < L.nrb) {  // uniform
-        const int64_t slot = ((int64_t)rbg * L.spr + s) * 32 + rl;
-        c.mw[rb] = L.mask32[2 * slot + g];
+        const int64_t u = (int64_t)rbg * L.spr + s;  // uniform
+        c.mw[rb] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(L.mask32) + u * 256 + m_lane_off);
 #pragma unroll
-        for (int p = 0; p < Q; ++p) c.x[rb][p] = load_enc(L.enc + ((int64_t)p * L.n_slots + slot) * L.nib, L.nib);
+        for (int p = 0; p < Q; ++p) {
+          // one (possibly unaligned) dword; the bytes past n_in/8 belong to the next slots or to
+          // the padding at the end of the buffer and are ignored by the table lookups below
+          const uint8_t *src = L.enc + ((int64_t)p * L.n_slots + u * 32) * L.nib + e_lane_off;
+          uint32_t x;
+          __builtin_memcpy(&x, src, 4);
+          c.x[rb][p] = x;
+        }
       }
     }
   };
 
   // per-lane byte offset of the transposing reads inside the wave's buffer (see lds_read_tr16)
   const int jj = (lane >> 2) & 3, c4 = lane & 3;
-  const int tr_base = (32 * g + 2 * (jj >> 1) + 16 * (jj & 1)) * RSB + (16 * ((lane >> 4) & 1) + 4 * c4) * 2;
+  const uint8_t *tr_ptr =
+      xbuf + (32 * g + 2 * (jj >> 1) + 16 * (jj & 1)) * RSB + (16 * ((lane >> 4) & 1) + 4 * c4) * 2;
+  const uint32_t lut_lane = (uint32_t)g;
 
+  // X (8*NCB registers per lane and slice) and the compressed words are fetched one slice ahead.
   Comp nxt;
   if (cnt > 0) {
-    load_x(w0);
     load_comp(w0, nxt);
+    load_x(w0);
   }
   for (int s = w0; s < w1; ++s) {
     store_x();  // LDS ops of one wave execute in order: the reads of the previous slice are done
     const Comp cur = nxt;
     if (s + 1 < w1) {  // next slice in flight while this one is consumed
-      load_x(s + 1);
       load_comp(s + 1, nxt);
+      load_x(s + 1);
     }
     // decrypt, patch, interleave with the mask
     uint32_t Iw[RB][Q][2];
@@ -234,8 +258,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
         const uint32_t x = cur.x[rb][p];
-        uint32_t S = 0;
-        for (int b = 0; b < L.nib; ++b) S ^= lut[2 * ((b << 8) + ((x >> (8 * b)) & 255)) + g];
+        uint32_t S = lut[2 * (x & 255) + lut_lane];
+        if (L.nib > 1) S ^= lut[2 * (256 + ((x >> 8) & 255)) + lut_lane];  // uniform branches
+        if (L.nib > 2) S ^= lut[2 * (512 + ((x >> 16) & 255)) + lut_lane];
+        if (L.nib > 3) S ^= lut[2 * (768 + (x >> 24)) + lut_lane];
         uint32_t pa, pe, base;
         if (pre_ok) {
           base = __builtin_amdgcn_readlane(offv[rb][p], 0);
@@ -255,7 +281,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
           const uint32_t rel = i - base;
           const uint32_t v = (pre_ok && rel < 64u) ? (uint32_t)__builtin_amdgcn_readlane(entv[rb][p], rel)
                                                    : (uint32_t)L.patch[i];
-          if ((int)(v >> 6) == rl && (int)((v >> 5) & 1) == g) S ^= 1u << (v & 31);
+          if ((v >> 5) == (uint32_t)(rl * 2 + g)) S ^= 1u << (v & 31);
         }
         const uint32_t mw = cur.mw[rb];
         Iw[rb][p][0] = (mw & 0x55555555u) | ((S << 1) & 0xAAAAAAAAu);
@@ -267,7 +293,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       bf16x8 bfrag[NCB];
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
-        const uint8_t *src = xbuf + tr_base + (8 * h + par) * RSB + cb * 64;
+        const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
         const s16x4 lo = lds_read_tr16(src);            // operand slots 0..3
         const s16x4 hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
         bfrag[cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -366,8 +392,12 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
     const int32_t rc = xorenc_internal_check_launch();
     if (rc != XORENC_OK) return rc;
   }
-  hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW>), dim3(row_groups, col_groups, ks), dim3(NW * 64), 0, st, D, X,
-                     ldx, B, Y, ldy, sps, ks > 1 ? 1 : 0, x_fast);
+  if (x_fast)
+    hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, true>), dim3(row_groups, col_groups, ks), dim3(NW * 64), 0,
+                       st, D, X, ldx, B, Y, ldy, sps, ks > 1 ? 1 : 0);
+  else
+    hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, false>), dim3(row_groups, col_groups, ks), dim3(NW * 64), 0,
+                       st, D, X, ldx, B, Y, ldy, sps, ks > 1 ? 1 : 0);
   return xorenc_internal_check_launch();
 }
 
@@ -404,6 +434,8 @@ extern "C" int32_t xorenc_spmm(const xorenc_layer *layer, const void *X, int32_t
   const int32_t rc = xorenc_fill_dev_layer(layer, &D);
   if (rc != XORENC_OK) return rc;
   if (!X || !Y || B <= 0 || ldx < B || ldy < B) return XORENC_EINVAL;
+  // X is addressed through a buffer descriptor with 32-bit offsets
+  if ((int64_t)layer->n * ldx * (x_dtype == XORENC_X_F32 ? 4 : 2) >= ((int64_t)1 << 32)) return XORENC_EUNSUPPORTED;
   if (x_dtype != XORENC_X_F32 && x_dtype != XORENC_X_BF16) return XORENC_EUNSUPPORTED;
   if (((uintptr_t)Y & 3) || ((uintptr_t)X & (x_dtype == XORENC_X_F32 ? 3 : 1))) return XORENC_EALIGN;
   // 16-byte loads of X need whole chunks (8 bf16 / 4 fp32 columns) and 16-byte aligned rows
