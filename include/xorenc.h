@@ -54,8 +54,6 @@ enum { XORENC_X_F32 = 0, XORENC_X_BF16 = 1 };
  * position of one row block (32 slices, one per row). */
 #define XORENC_ROWS_PER_UNIT 32
 #define XORENC_N_OUT 64
-/* Bytes of zero padding that follow the last encrypted slice in `enc` (kernels read whole dwords). */
-#define XORENC_ENC_PAD 16
 
 /*
  * One encrypted weight matrix in the packed device layout.
@@ -69,9 +67,8 @@ enum { XORENC_X_F32 = 0, XORENC_X_BF16 = 1 };
  *
  *   mask      DEV  uint64[n_slots], 8-byte aligned.  Bit j of mask[slot(r,s)] = 1 iff weight
  *                  (r, 64 s + j) is kept (care); padding rows/columns are 0.
- *   enc       DEV  uint8[q][n_slots][n_in/8] followed by XORENC_ENC_PAD readable bytes: the n_in
- *                  encrypted bits of each slice of each plane, little endian (bit j of the integer
- *                  = x_j).  2-byte aligned for n_in = 16, 4-byte aligned for n_in = 32.
+ *   enc       DEV  uint8[q][n_slots][n_in/8]: the n_in encrypted bits of each slice of each
+ *                  plane, little endian (bit j of the integer = x_j).  4-byte aligned.
  *   patch_off DEV  uint32[q*n_units + 1], 4-byte aligned, non-decreasing;
  *                  entries [patch_off[p*n_units+u], patch_off[p*n_units+u+1]) belong to unit u
  *                  of plane p.
@@ -100,7 +97,7 @@ typedef struct xorenc_layer {
 /* Element counts of the packed buffers for a shape (HOST arithmetic only). */
 typedef struct xorenc_sizes {
   int64_t n_pad, m_pad, spr, n_slots, n_units;
-  int64_t enc_bytes;       /* q*n_slots*n_in/8 + XORENC_ENC_PAD */
+  int64_t enc_bytes;       /* q*n_slots*n_in/8 */
   int64_t mask_words;      /* n_slots */
   int64_t patch_off_words; /* q*n_units + 1 */
 } xorenc_sizes;
@@ -155,7 +152,7 @@ XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, const uint8_t *a, int6
  *   M_rows     HOST uint32[64]
  *   mask       DEV  uint64[n_slots]      care mask, unit-major (the layer's mask buffer itself)
  *   planes     DEV  uint64[q][n_slots]   quantised bits, unit-major; bits at pruned positions are ignored
- *   enc_out    DEV  uint8[q][n_slots][n_in/8] (+ XORENC_ENC_PAD bytes that the encoder leaves untouched)
+ *   enc_out    DEV  uint8[q][n_slots][n_in/8]
  *   patch_off_out DEV uint32[q*n_units + 1]
  *   patch_out  DEV  uint16[patch_capacity]; entries beyond the capacity are not written.  The caller
  *              must compare patch_off_out[q*n_units] (the true total) with patch_capacity after the

@@ -3,11 +3,20 @@ import os
 import shutil
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libxorenc.so")
-SOURCES = ["xorenc_host.cpp", "xorenc_decode.hip", "xorenc_spmm.hip", "xorenc_encode.hip"]
+SOURCES = ["xorenc_host.cpp", "xorenc_decode.hip", "xorenc_encode.hip", "xorenc_spmm.hip",
+           "xorenc_spmm_q1.hip", "xorenc_spmm_q2.hip", "xorenc_spmm_q3.hip", "xorenc_spmm_q4.hip"]
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics", "-fvisibility=hidden",
+    # packed fp32 VALU forms are kept out of the generated code on purpose
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
 
 
 def hipcc_path() -> str:
@@ -17,22 +26,27 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found; libxorenc.so cannot be built")
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source for gfx950 into one shared library; returns its path."""
-    cmd = [
-        hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-        "-munsafe-fp-atomics", "-fvisibility=hidden",
-        # packed fp32 VALU forms are kept out of the generated code on purpose
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wno-unused-function",
-        "-x", "hip",
-    ] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH + ".tmp"]
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+        raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + out)
+    return out
+
+
+def build_library(verbose: bool = False, jobs: int = 8) -> str:
+    """Compile every HIP source for gfx950 (objects in parallel) and link one shared library."""
+    hipcc = hipcc_path()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+    cmds = [[hipcc] + FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(cmds)))) as ex:
+        outs = list(ex.map(_run, cmds))
+    outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH + ".tmp"]))
+    if verbose:
+        for o in outs:
+            if o.strip():
+                print(o)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
 

@@ -28,8 +28,7 @@ int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   if (sz.n_slots > (int64_t)1 << 31) return XORENC_EUNSUPPORTED;
   const int nib = layer->n_in / 8;
   if (((uintptr_t)layer->mask & 7) || ((uintptr_t)layer->patch_off & 3) || ((uintptr_t)layer->alpha & 3) ||
-      ((uintptr_t)layer->patch & 1) || (nib == 2 && ((uintptr_t)layer->enc & 1)) ||
-      (nib == 4 && ((uintptr_t)layer->enc & 3)))
+      ((uintptr_t)layer->patch & 1) || ((uintptr_t)layer->enc & 3))
     return XORENC_EALIGN;
   D->enc = layer->enc;
   D->mask32 = reinterpret_cast<const uint32_t *>(layer->mask);

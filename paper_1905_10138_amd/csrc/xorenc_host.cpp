@@ -32,7 +32,7 @@ int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, xorenc_s
   out->spr = spr;
   out->n_slots = nrb * 32 * spr;
   out->n_units = nrb * spr;
-  out->enc_bytes = (int64_t)q * out->n_slots * (n_in / 8) + XORENC_ENC_PAD;
+  out->enc_bytes = (int64_t)q * out->n_slots * (n_in / 8);
   out->mask_words = out->n_slots;
   out->patch_off_words = (int64_t)q * out->n_units + 1;
   return XORENC_OK;

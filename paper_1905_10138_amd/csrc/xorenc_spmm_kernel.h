@@ -1,0 +1,585 @@
+// Fused decrypt + patch + mask + dequantise + W X kernel for the gfx950 matrix cores
+// (arXiv 1905.10138: Sections 3.1-3.2 for the decode, Fig. 1 for the product it feeds).
+// Included by the per-Q instantiation units xorenc_spmm_q*.hip.
+//
+// Operand synthesis.  The MFMA A operand is built in registers as bf16 values -2*t, t in
+// {-1,0,+1} the ternary weight of one bit-plane: bit 15 = quantised bit, bit 14 = mask bit, all
+// other bits 0 (0xC000 = -2, 0x4000 = +2, 0x0000 / 0x8000 = +-0).  The factor -1/2 is folded into
+// alpha in the fp32 epilogue, so the scales are never rounded to bf16.
+//
+// Work decomposition.  A workgroup of NW waves owns RB row blocks of 32 rows and CW = 32*NCB
+// columns of X.  The waves split the reduction dimension into contiguous slice ranges and are
+// fully independent until the final reduction: each wave streams the 64 rows of X that belong to
+// its current slice through a private LDS buffer (global -> registers PD slices ahead, registers
+// -> LDS, LDS -> operand registers with the transposing LDS read), so the main loop has no
+// workgroup barrier.  Lane (rl = lane%32, g = lane/32) holds the 32-bit half g of the slice of
+// row rl of each row block.
+//
+// One 32-bit half feeds 4 MFMA steps t = 2*par + h.  With I_par the word whose bit pairs
+// (2a, 2a+1) hold (mask, sign) of half-word bit 2a+par, operand dword d of step t is
+// (I_par << (14 - 2*(4h+d))) & 0xC000C000: its low element is half-word bit 8h+2d+par, its high
+// element bit 8h+2d+par+16.  So operand slot j of step t of half g is the W column (X row)
+//     64 s + 32 g + 8 h + par + 2 (j>>1) + 16 (j&1)
+// and the B operand is gathered from exactly those X rows.
+//
+// Addressing.  Every global load in the loop is a buffer load: (descriptor) + (per-lane 32-bit
+// offset fixed for the whole kernel) + (uniform scalar offset), so the loop spends no vector
+// instructions on addresses, and loads beyond the end of X return zero (rows of the padded last
+// slice) instead of needing a branch.
+#ifndef XORENC_SPMM_KERNEL_H
+#define XORENC_SPMM_KERNEL_H
+
+#include "xorenc_device.h"
+
+namespace xorenc_spmm_detail {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr uint32_t kRsrcFlags = 0x00020000u;  // raw buffer, 32-bit data format
+
+// Transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of the 8 bytes
+// addressed by lanes 4j + i/4, j = 0..3.
+__device__ inline s16x4 lds_read_tr16(const uint8_t *p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
+}
+
+template <bool V>
+struct BoolC {
+  static constexpr bool value = V;
+};
+
+// NIBT = n_in/8 known at compile time (1..4), or 0: read it from the layer at run time.
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT>
+__global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
+                                                      float *__restrict__ Y, int64_t ldy, int slices_per_split,
+                                                      int use_atomic) {
+  constexpr int CW = 32 * NCB;                 // bf16 columns held in LDS per X row
+  constexpr int RSB = CW * 2 + 16;             // LDS row stride in bytes (16 bytes of padding)
+  constexpr int XBUF = 64 * RSB;               // one wave's buffer: the 64 X rows of a slice
+  constexpr int ROWS = 32 * RB;
+  constexpr int NR = XF32 ? CW / 3 : CW;       // real X columns per workgroup
+  constexpr int NCH = XF32 ? NR / 4 : CW / 8;  // 16-byte chunks per X row in global memory
+  constexpr int RPI = 64 / NCH;                // rows covered by one load instruction of the wave (XFAST)
+  constexpr int EPC = XF32 ? 4 : 8;            // X elements per chunk
+  constexpr int ESZ = XF32 ? 4 : 2;            // bytes per X element
+  constexpr int NIBMAX = NIBT ? NIBT : 4;
+  constexpr int TS = CW + 8;                   // row stride (floats) of a reduction tile
+  constexpr int TILE = ROWS * TS;
+  constexpr int FIT = (NW * XBUF) / (TILE * 4);
+  constexpr int NREG = FIT >= 8 ? (NW < 8 ? NW : 8) : (FIT >= 4 ? 4 : (FIT >= 2 ? 2 : 1));
+  static_assert(!XF32 || NCB % 3 == 0, "fp32 X uses three bf16 terms per column");
+  static_assert(FIT >= 1, "a reduction tile must fit in the X buffers");
+  static_assert(NW % NREG == 0, "waves must split evenly over the reduction tiles");
+  __shared__ __attribute__((aligned(16))) uint8_t xbuf_all[NW * XBUF];
+  __shared__ uint32_t lut[NIBMAX * 512];
+  __shared__ __attribute__((aligned(16))) float alpha_s[Q * ROWS];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, rl = lane & 31;
+  const int row0 = blockIdx.x * ROWS;
+  const int col0 = blockIdx.y * NR;  // first real X column of this workgroup
+  const int nib = NIBT ? NIBT : L.nib;
+  uint8_t *xbuf = xbuf_all + wave * XBUF;
+
+  // ---- this wave's contiguous slice range [w0, w1) inside the workgroup's [s_begin, s_end)
+  const int s_begin = blockIdx.z * slices_per_split;
+  const int s_end = min(L.spr, s_begin + slices_per_split);
+  const int per_wave = (s_end - s_begin + NW - 1) / NW;
+  const int w0 = min(s_end, s_begin + wave * per_wave);
+  const int w1 = min(s_end, w0 + per_wave);
+  const int cnt = w1 - w0;
+
+  // ---- buffer descriptors
+  const int64_t row_bytes = ldx * ESZ;
+  const uint32_t x_extent = (uint32_t)((int64_t)(L.n - 1) * row_bytes + (int64_t)(B - col0) * ESZ);
+  const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t *>(static_cast<const uint8_t *>(Xv) + (int64_t)col0 * ESZ), 0, x_extent, kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t *>(L.mask32), 0, (uint32_t)(L.n_slots * 8), kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t ersrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t *>(L.enc), 0, (uint32_t)(L.n_slots * L.q * nib), kRsrcFlags);
+
+  // ---- X loader.  One slice = 64 rows of X.  Chunk = 16 bytes of a row (8 bf16 / 4 fp32 columns).
+  // XFAST: chunk i of a lane is (row i*RPI + lane/NCH, chunk lane%NCH), 16-byte loads.
+  // otherwise: lane = row, chunk i is walked element by element (any B, ldx, alignment).
+  // Chunks that lie beyond column B are redirected to chunk 0 (in bounds); what they put into the
+  // padded X columns only reaches output columns that are never stored.
+  // Register-light variants fetch the first two slices at once; the others fetch the second
+  // slice only after the first has been copied to LDS.
+  constexpr bool PRO2 = (NCH <= 8) && !XF32;
+  uint4 xr[NCH];                // X rows of the slice after the one in LDS
+  uint4 xr0[PRO2 ? NCH : 1];    // prologue only: X rows of the first slice
+  const int xrow = XFAST ? lane / NCH : lane;
+  const int xch = XFAST ? lane % NCH : 0;
+  const uint32_t x_lane_off = (uint32_t)(xrow * row_bytes) + ((col0 + xch * EPC < B) ? xch * 16 : 0);
+  const uint32_t x_lds_off = XFAST ? (uint32_t)(xrow * RSB + xch * 16) : (uint32_t)(lane * RSB);
+  auto load_x = [&](int s, uint4(&xr)[NCH]) {
+    const uint32_t sbase = (uint32_t)(s * 64 * row_bytes);  // uniform
+    if constexpr (XFAST) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const u32x4 v =
+            __builtin_amdgcn_raw_buffer_load_b128(xrsrc, x_lane_off, sbase + (uint32_t)(i * RPI * row_bytes), 0);
+        xr[i] = make_uint4(v[0], v[1], v[2], v[3]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        uint32_t h[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+          h[e] = 0u;
+          if (col0 + i * EPC + e < B) {  // uniform
+            const uint32_t so = sbase + (uint32_t)((i * EPC + e) * ESZ);
+            if constexpr (XF32)
+              h[e] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, x_lane_off, so, 0);
+            else
+              h[e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(xrsrc, x_lane_off, so, 0);
+          }
+        }
+        if constexpr (XF32)
+          xr[i] = make_uint4(h[0], h[1], h[2], h[3]);
+        else
+          xr[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+      }
+    }
+  };
+  auto store_x = [&](const uint4(&xr)[NCH]) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      // XFAST: row advances by RPI per i, chunk fixed; otherwise row fixed, chunk = i
+      const int ch = XFAST ? xch : i;
+      uint8_t *dst_row = xbuf + x_lds_off + (XFAST ? i * RPI * RSB : 0);
+      if constexpr (!XF32) {
+        *reinterpret_cast<uint4 *>(dst_row + (XFAST ? 0 : i * 16)) = xr[i];
+      } else {
+        // exact split of each fp32 value into three bf16 terms: hi + mid + lo
+        const uint32_t f[4] = {xr[i].x, xr[i].y, xr[i].z, xr[i].w};
+        uint32_t part[3][4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v0 = __uint_as_float(f[e]);
+          const uint32_t h0 = f32_to_bf16_rne(v0);
+          const float r1 = v0 - __uint_as_float(h0 << 16);
+          const uint32_t h1 = f32_to_bf16_rne(r1);
+          const float r2 = r1 - __uint_as_float(h1 << 16);
+          part[0][e] = h0;
+          part[1][e] = h1;
+          part[2][e] = f32_to_bf16_rne(r2);
+        }
+        // real column 4*ch+e of the tile -> LDS column part*32 + 4*ch + e (NR = 32 real columns)
+        uint8_t *row_base = XFAST ? dst_row - xch * 16 : dst_row;
+#pragma unroll
+        for (int pt = 0; pt < 3; ++pt) {
+          const uint2 w2 = make_uint2(part[pt][0] | (part[pt][1] << 16), part[pt][2] | (part[pt][3] << 16));
+          *reinterpret_cast<uint2 *>(row_base + (pt * 32 + 4 * ch) * 2) = w2;
+        }
+      }
+    }
+  };
+
+  // ---- compressed words of one slice for this lane: mask half and the dword(s) holding its
+  // encrypted bits (the n_in bits of slot rl start at byte rl*nib of the unit's run)
+  struct Comp {
+    uint32_t mw[RB];
+    uint32_t e0[RB][Q];
+    uint32_t e1[RB][Q];  // second dword, only needed when a 3-byte field straddles two dwords
+  };
+  const bool two_dw = NIBT ? (NIBT == 3) : (nib == 3);
+  const uint32_t m_lane_off = (uint32_t)(rl * 8 + g * 4);
+  const uint32_t e_byte = (uint32_t)(rl * nib);
+  const uint32_t e_lane_off = e_byte & ~3u;
+  const uint32_t e_shift = 8u * (e_byte & 3u);
+  auto load_comp = [&](int s, Comp &c) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const int rbg = blockIdx.x * RB + rb;
+      c.mw[rb] = 0u;
+#pragma unroll
+      for (int p = 0; p < Q; ++p) c.e0[rb][p] = c.e1[rb][p] = 0u;
+      if (rbg < L.nrb) {  // uniform
+        const uint32_t u = (uint32_t)(rbg * L.spr + s);  // uniform
+        c.mw[rb] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_lane_off, u * 256u, 0);
+#pragma unroll
+        for (int p = 0; p < Q; ++p) {
+          const uint32_t so = ((uint32_t)p * (uint32_t)L.n_slots + u * 32u) * (uint32_t)nib;
+          c.e0[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so, 0);
+          if (two_dw) c.e1[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so + 4u, 0);
+        }
+      }
+    }
+  };
+
+  // ---- first loads go out before anything else so that they overlap the table build
+  Comp ring[2];
+  if (cnt > 0) {
+    load_comp(w0, ring[0]);
+    if constexpr (PRO2)
+      load_x(w0, xr0);
+    else
+      load_x(w0, xr);
+  }
+  if (cnt > 1) {
+    load_comp(w0 + 1, ring[1]);
+    if constexpr (PRO2) load_x(w0 + 1, xr);
+  }
+  // patch offsets of the whole range: lane i holds the offset of unit i of the range
+  const bool pre_ok = cnt <= 63;  // uniform
+  uint32_t offv[RB][Q];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int rbg = blockIdx.x * RB + rb;
+#pragma unroll
+    for (int p = 0; p < Q; ++p) {
+      offv[rb][p] = 0u;
+      if (rbg < L.nrb && pre_ok && cnt > 0) {
+        const uint32_t *po = L.patch_off + ((int64_t)p * L.n_units + (int64_t)rbg * L.spr + w0);
+        if (lane <= cnt) offv[rb][p] = po[lane];
+      }
+    }
+  }
+
+  // ---- XOR tables T_b[v] = XOR of the columns 8b..8b+7 of M selected by the bits of v, and alpha
+  for (int b = 0; b < nib; ++b)  // uniform
+    for (int v = tid; v < 256; v += NW * 64) {
+      uint32_t lo = 0, hi = 0;
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if ((v >> t) & 1) {
+          lo ^= L.Mcol_lo[8 * b + t];
+          hi ^= L.Mcol_hi[8 * b + t];
+        }
+      lut[2 * (b * 256 + v)] = lo;
+      lut[2 * (b * 256 + v) + 1] = hi;
+    }
+  for (int i = tid; i < Q * ROWS; i += NW * 64) {
+    const int p = i / ROWS, r = row0 + i % ROWS;
+    alpha_s[i] = (r < L.m) ? -0.5f * L.alpha[(int64_t)p * L.m + r] : 0.f;
+  }
+  __syncthreads();
+
+  // ---- patch entries of the range: lane j holds the j-th entry (relative to the range start).
+  // A range with more than 63 units or more than 64 entries of one (row block, plane) reads its
+  // lists from memory inside the loop instead.
+  uint32_t offrel[RB][Q], entv[RB][Q];
+  bool pfast = pre_ok;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int p = 0; p < Q; ++p) {
+      const uint32_t base = __builtin_amdgcn_readlane(offv[rb][p], 0);
+      const uint32_t total = __builtin_amdgcn_readlane(offv[rb][p], pre_ok ? cnt : 0) - base;
+      offrel[rb][p] = offv[rb][p] - base;
+      entv[rb][p] = 0u;
+      if (total > 64u) pfast = false;
+      if ((uint32_t)lane < min(total, 64u)) entv[rb][p] = (L.patch + base)[lane];
+    }
+
+  f32x16 acc[Q][RB][NCB];
+#pragma unroll
+  for (int p = 0; p < Q; ++p)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[p][rb][cb][i] = 0.f;
+
+  // per-lane address of the transposing reads inside the wave's buffer (see lds_read_tr16)
+  const int jj = (lane >> 2) & 3, c4 = lane & 3;
+  const uint8_t *tr_ptr =
+      xbuf + (32 * g + 2 * (jj >> 1) + 16 * (jj & 1)) * RSB + (16 * ((lane >> 4) & 1) + 4 * c4) * 2;
+  const uint32_t *lut_g = lut + g;
+  const uint32_t lane_id5 = (uint32_t)(rl * 2 + g);  // (row, half) as it appears in a patch entry
+
+  auto main_loop = [&](auto pf_tag) {
+    constexpr bool PF = decltype(pf_tag)::value;
+    uint32_t pcur[RB][Q];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int p = 0; p < Q; ++p) pcur[rb][p] = 0u;
+    // LDS holds the X rows of the slice about to be consumed, xr those of the one after it, and
+    // the loads of the slice after that are issued as soon as xr has been copied to LDS.
+    if constexpr (PRO2) {
+      if (cnt > 0) store_x(xr0);
+    } else {
+      if (cnt > 0) store_x(xr);
+      if (cnt > 1) load_x(w0 + 1, xr);
+    }
+    for (int sb = w0; sb < w1; sb += 2) {
+#pragma unroll
+      for (int d = 0; d < 2; ++d) {
+        const int s = sb + d;
+        if (s >= w1) break;  // uniform
+        const Comp cur = ring[d];
+        // decrypt: table look-ups first (LDS latency overlaps the operand reads below)
+        uint32_t Sx[RB][Q];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int p = 0; p < Q; ++p) {
+            uint32_t x;
+            if (two_dw)
+              x = __builtin_amdgcn_alignbit(cur.e1[rb][p], cur.e0[rb][p], e_shift);
+            else
+              x = cur.e0[rb][p] >> e_shift;
+            uint32_t S;
+            if constexpr (NIBT == 1) {
+              S = lut_g[2 * (x & 255)];
+            } else if constexpr (NIBT == 2) {
+              const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+              S = t0 ^ t1;
+            } else if constexpr (NIBT == 3) {
+              const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+              const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))];
+              S = t0 ^ t1 ^ t2;
+            } else if constexpr (NIBT == 4) {
+              const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+              const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))], t3 = lut_g[2 * (768 + (x >> 24))];
+              S = t0 ^ t1 ^ t2 ^ t3;
+            } else {
+              S = lut_g[2 * (x & 255)];
+              if (nib > 1) S ^= lut_g[2 * (256 + ((x >> 8) & 255))];  // uniform branches
+              if (nib > 2) S ^= lut_g[2 * (512 + ((x >> 16) & 255))];
+              if (nib > 3) S ^= lut_g[2 * (768 + (x >> 24))];
+            }
+            Sx[rb][p] = S;
+          }
+        // The B operands are pulled into registers GS steps at a time; once the last group is
+        // out of LDS the buffer is free for the next slice, whose global loads are then re-armed.
+        constexpr int GS = (NCB >= 3) ? 1 : 4 / NCB;
+        uint32_t Iw[RB][Q][2];
+#pragma unroll
+        for (int t0 = 0; t0 < 4; t0 += GS) {
+          bf16x8 bfrag[GS][NCB];
+#pragma unroll
+          for (int tt = 0; tt < GS; ++tt) {
+            const int t = t0 + tt, par = t >> 1, h = t & 1;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+              const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
+              const s16x4 lo = lds_read_tr16(src);            // operand slots 0..3
+              const s16x4 hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
+              bfrag[tt][cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+          }
+          if (t0 + GS == 4) {
+            if (s + 1 < w1) store_x(xr);  // LDS ops of a wave execute in order: the reads above are done
+            if (s + 2 < w1) {             // refill
+              load_comp(s + 2, ring[d]);
+              load_x(s + 2, xr);
+            }
+          }
+          if (t0 == 0) {
+            // patch flips, then interleave sign and mask bits
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+              for (int p = 0; p < Q; ++p) {
+                uint32_t S = Sx[rb][p];
+                if constexpr (PF) {
+                  const uint32_t pe = __builtin_amdgcn_readlane(offrel[rb][p], s - w0 + 1);
+                  for (uint32_t j = pcur[rb][p]; j < pe; ++j) {
+                    const uint32_t v = __builtin_amdgcn_readlane(entv[rb][p], j);
+                    if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
+                  }
+                  pcur[rb][p] = pe;
+                } else {
+                  const int rbg = blockIdx.x * RB + rb;
+                  if (rbg < L.nrb) {
+                    const int64_t u = (int64_t)p * L.n_units + (int64_t)rbg * L.spr + s;
+                    const uint32_t pa = __builtin_amdgcn_readfirstlane(L.patch_off[u]);
+                    const uint32_t pe = __builtin_amdgcn_readfirstlane(L.patch_off[u + 1]);
+                    for (uint32_t j = pa; j < pe; ++j) {
+                      const uint32_t v = L.patch[j];
+                      if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
+                    }
+                  }
+                }
+                const uint32_t mw = cur.mw[rb];
+                Iw[rb][p][0] = (mw & 0x55555555u) | ((S << 1) & 0xAAAAAAAAu);
+                Iw[rb][p][1] = ((mw >> 1) & 0x55555555u) | (S & 0xAAAAAAAAu);
+              }
+          }
+#pragma unroll
+          for (int tt = 0; tt < GS; ++tt) {
+            const int t = t0 + tt, par = t >> 1, h = t & 1;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+              for (int p = 0; p < Q; ++p) {
+                const uint32_t I = Iw[rb][p][par];
+                u32x4 a;
+#pragma unroll
+                for (int dd = 0; dd < 4; ++dd) a[dd] = (I << (14 - 2 * (4 * h + dd))) & 0xC000C000u;
+                const bf16x8 afrag = __builtin_bit_cast(bf16x8, a);
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                  acc[p][rb][cb] =
+                      __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[tt][cb], acc[p][rb][cb], 0, 0, 0);
+              }
+          }
+        }
+      }
+    }
+  };
+  if (pfast)
+    main_loop(BoolC<true>{});
+  else
+    main_loop(BoolC<false>{});
+
+  // ---- epilogue: scale by alpha (fp32) and reduce the waves in a fixed order.  NREG tiles of
+  // ROWS x TS floats live in the (now idle) X buffers; wave w adds into tile w % NREG in round
+  // w / NREG, then every thread sums the NREG tiles of its outputs in ascending tile order.
+  // acc element i of a lane is row 8*(i/4) + 4*g + i%4, column rl of its 32x32 block.
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int j4 = 0; j4 < 4; ++j4) {
+      f32x4 a4[Q];
+#pragma unroll
+      for (int p = 0; p < Q; ++p)
+        a4[p] = *reinterpret_cast<const f32x4 *>(alpha_s + p * ROWS + rb * 32 + 8 * j4 + 4 * g);
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          float v = a4[0][k] * acc[0][rb][cb][4 * j4 + k];
+#pragma unroll
+          for (int p = 1; p < Q; ++p) v += a4[p][k] * acc[p][rb][cb][4 * j4 + k];
+          acc[0][rb][cb][4 * j4 + k] = v;  // plane 0's accumulator now holds the scaled sum
+        }
+    }
+  __syncthreads();
+  float *red = reinterpret_cast<float *>(xbuf_all);
+  for (int round = 0; round < NW / NREG; ++round) {
+    if (wave / NREG == round) {
+      float *tile = red + (wave % NREG) * TILE;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            float *dst = tile + (rb * 32 + 8 * (i >> 2) + 4 * g + (i & 3)) * TS + cb * 32 + rl;
+            if (round == 0)
+              *dst = acc[0][rb][cb][i];
+            else
+              *dst += acc[0][rb][cb][i];
+          }
+    }
+    __syncthreads();
+  }
+  auto reduced = [&](int off) {
+    float v = red[off];
+#pragma unroll
+    for (int r = 1; r < NREG; ++r) v += red[r * TILE + off];
+    return v;
+  };
+  for (int idx = tid; idx < ROWS * NR; idx += NW * 64) {
+    const int row = idx / NR, nn = idx % NR;
+    const int gr = row0 + row, gc = col0 + nn;
+    if (gr < L.m && gc < B) {
+      float v;
+      if (XF32) {
+        const int o = row * TS + 96 * (nn >> 5) + (nn & 31);
+        v = (reduced(o) + reduced(o + 32)) + reduced(o + 64);
+      } else {
+        v = reduced(row * TS + nn);
+      }
+      float *dst = Y + (int64_t)gr * ldy + gc;
+      if (use_atomic)
+        unsafeAtomicAdd(dst, v);
+      else
+        *dst = v;
+    }
+  }
+}
+
+static __global__ void zero_rows_kernel(float *Y, int64_t ldy, int m, int B) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)m * B) Y[(i / B) * ldy + (i % B)] = 0.f;
+}
+
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT>
+inline void launch_variant(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, dim3 grid,
+                           int sps, int atomic, hipStream_t st) {
+  hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, XFAST, PD, NIBT>), grid, dim3(NW * 64), 0, st, D, X, ldx, B,
+                     Y, ldy, sps, atomic);
+}
+
+template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2>
+int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, int x_fast,
+                    hipStream_t st) {
+  constexpr int NR = XF32 ? (32 * NCB) / 3 : 32 * NCB;
+  const int row_groups = (D.nrb + RB - 1) / RB;
+  const int col_groups = (B + NR - 1) / NR;
+  // split the reduction dimension across workgroups only when the tile grid alone cannot fill
+  // the chip; every wave should still own at least one slice
+  int ks = 1;
+  const int base = row_groups * col_groups;
+  const int max_ks = (D.spr + NW - 1) / NW;
+  if (base < 256) ks = max(1, min(max_ks, (512 + base - 1) / base));
+  int sps = (D.spr + ks - 1) / ks;
+  sps = (sps + NW - 1) / NW * NW;
+  ks = (D.spr + sps - 1) / sps;
+  if (ks > 1) {
+    const int64_t tot = (int64_t)D.m * B;
+    hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, Y, ldy, D.m, B);
+    const int32_t rc = xorenc_internal_check_launch();
+    if (rc != XORENC_OK) return rc;
+  }
+  const dim3 grid(row_groups, col_groups, ks);
+  const int atomic = ks > 1 ? 1 : 0;
+  if (!x_fast) {
+    launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+  } else {
+    switch (D.nib) {
+      case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+      case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+      case 3: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+      default: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+    }
+  }
+  return xorenc_internal_check_launch();
+}
+
+// Tile shapes per (Q, column blocks): Q*RB*NCB accumulator sets of 16 registers must leave room
+// for the X prefetch registers at two waves per SIMD.
+template <int Q>
+int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
+                        int x_fast, hipStream_t st) {
+  if (x_dtype == XORENC_X_F32) {
+    if constexpr (Q <= 2)
+      return launch_spmm<3, Q, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
+    else
+      return launch_spmm<3, Q, 1, true, 4>(D, X, ldx, B, Y, ldy, x_fast, st);
+  }
+  const int blocks = (B + 31) / 32;
+  if constexpr (Q == 1) {
+    if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (blocks == 2) return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    return launch_spmm<4, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+  } else if constexpr (Q == 2) {
+    if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    return launch_spmm<2, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+  } else if constexpr (Q == 3) {
+    return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+  } else {
+    return launch_spmm<1, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+  }
+}
+
+}  // namespace xorenc_spmm_detail
+
+// one translation unit per Q instantiates these
+int32_t xorenc_spmm_dispatch_q1(const DevLayer &, const void *, int32_t, int64_t, int, float *, int64_t, int, hipStream_t);
+int32_t xorenc_spmm_dispatch_q2(const DevLayer &, const void *, int32_t, int64_t, int, float *, int64_t, int, hipStream_t);
+int32_t xorenc_spmm_dispatch_q3(const DevLayer &, const void *, int32_t, int64_t, int, float *, int64_t, int, hipStream_t);
+int32_t xorenc_spmm_dispatch_q4(const DevLayer &, const void *, int32_t, int64_t, int, float *, int64_t, int, hipStream_t);
+
+#endif

@@ -1,0 +1,7 @@
+// Instantiates the fused decode + product kernels for layers with 4 bit-planes.
+#include "xorenc_spmm_kernel.h"
+
+int32_t xorenc_spmm_dispatch_q4(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y,
+                                int64_t ldy, int x_fast, hipStream_t st) {
+  return xorenc_spmm_detail::dispatch_spmm_q<4>(D, X, x_dtype, ldx, B, Y, ldy, x_fast, st);
+}

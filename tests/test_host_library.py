@@ -30,7 +30,7 @@ def test_sizes():
     s = xe.get_sizes(6000, 3000, 24, 3)
     assert (s["n_pad"], s["m_pad"], s["spr"]) == (3008, 6016, 47)
     assert s["n_slots"] == 6016 * 47 and s["n_units"] == 188 * 47
-    assert s["enc_bytes"] == 3 * s["n_slots"] * 3 + 16 and s["patch_off_words"] == 3 * s["n_units"] + 1
+    assert s["enc_bytes"] == 3 * s["n_slots"] * 3 and s["patch_off_words"] == 3 * s["n_units"] + 1
     for bad in [(0, 8, 8, 1), (8, 0, 8, 1)]:
         with pytest.raises(xe.XorencError) as e:
             xe.get_sizes(*bad)
