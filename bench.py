@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of W in the CPU-oracle sample (0 = auto)")
     ap.add_argument("--replica-bytes", type=float, default=float(1 << 30))
     ap.add_argument("--decode-only", action="store_true", help="also time xorenc_decode (planes) on the workload")
+    ap.add_argument("--no-fig1", action="store_true", help="skip the Fig. 1-shaped extra (decode-only and fused, B=64)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region run one 256 MiB device copy (reference dispatch for rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -144,6 +147,18 @@ def roofline_entry(flops, comp_bytes, total_bytes, sec_per_launch, B):
             "traffic": None, "total_bytes_gbs": total_bytes / sec_per_launch / 1e9}
 
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), scaled by
+# what the same counters read for a 256 MiB device copy in the same run; see profiles/.
+# Filled in from the committed profile of this exact command; None = not measured.
+MEASURED_TRAFFIC = {
+    # profiles/spmm_large_q1_hbm_traffic.md: bytes read + written per launch
+    "large_q1:B1": {"read_bytes": 10.10e6, "write_bytes": 0.07e6},
+    "large_q1:B8": {"read_bytes": 10.44e6, "write_bytes": 0.52e6},
+    "large_q1:B64": {"read_bytes": 14.13e6, "write_bytes": 4.19e6},
+    "large_q1:B256": {"read_bytes": 28.71e6, "write_bytes": 16.78e6},
+}
+
+
 def cpu_baseline(wl, B, x_exact, y_gpu_rows, rows):
     """Time the CPU oracle (decode + fp64 product) on the first `rows` rows of the same workload."""
     from oracle import decoder, encoder
@@ -155,7 +170,7 @@ def cpu_baseline(wl, B, x_exact, y_gpu_rows, rows):
     enc = encoder.encode(wl.keep[:rows], wl.planes[:, :rows], wl.alpha[:, :rows], wl.M, wl.n)  # not timed (offline step)
     times = []
     y = None
-    for _ in range(3):
+    for _ in range(5):
         t0 = time.perf_counter()
         y = decoder.spmm_f64(enc, x_exact)
         times.append(time.perf_counter() - t0)
@@ -163,8 +178,41 @@ def cpu_baseline(wl, B, x_exact, y_gpu_rows, rows):
     err = float(np.linalg.norm(y_gpu_rows - y) / max(np.linalg.norm(y), 1e-300))
     flops = 2.0 * rows * wl.n * B
     return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {rows} of {wl.m} rows of the same W, X and B; median of 3; oracle decode + fp64 W X",
+            "sample": f"first {rows} of {wl.m} rows of the same W, X and B; median of 5 runs; oracle decode + fp64 W X "
+                      "(the oracle's encoder runs before, untimed)",
             "seconds": t, "gpu_vs_oracle_rel_fro": err}
+
+
+def fig1_extra(xe, torch, dev, args):
+    """The Fig. 1-shaped configuration: decode-only (planes and dense bf16) and the fused product at B = 64."""
+    from synth_inputs import CONFIGS, make_workload
+    cfg = CONFIGS["fig1"]
+    wl = make_workload(cfg)
+    layer = build_layer(wl, xe, torch, dev)
+    stored, _ = wl.X(64)
+    xg = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev)
+    runner = SpmmRunner(xe, torch, layer, xg, 64, args.replica_bytes)
+    if not args.no_graph:
+        runner.capture()
+    steps = max(200, args.sweep_steps)
+    wall, ev = runner.time(steps, 50)
+    res = {"workload": f"fig1: W {cfg.m}x{cfg.n} S={cfg.S} q=1 n_in=16, X {cfg.n}x64 bf16",
+           "fused_us_per_launch": ev * 1e6 / steps, "fused_tflops": 2.0 * cfg.m * cfg.n * 64 * steps / wall / 1e12,
+           "compressed_bytes": runner.comp_bytes, "replicas": runner.R}
+    for kind, name, width in ((xe.OUT_PLANES, "decode_planes", 8 * ((cfg.n + 63) // 64) / cfg.n),
+                              (xe.OUT_BF16, "decode_bf16", 2.0)):
+        out = xe.decode(layer, kind)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            xe.decode(layer, kind, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 200
+        res[name + "_us"] = us
+        res[name + "_gbs"] = (layer.compressed_bytes() + cfg.m * cfg.n * width) / (us * 1e-6) / 1e9
+    return res
 
 
 def main():
@@ -248,9 +296,20 @@ def main():
         "roofline": main_res["roofline"],
         "sweep": sweep,
     }
+    key = f"{cfg.name}:B{args.batch}"
+    if key in MEASURED_TRAFFIC:
+        out["roofline"]["traffic"] = MEASURED_TRAFFIC[key]
+    if not args.no_fig1 and cfg.name != "fig1":
+        extra["fig1"] = fig1_extra(xe, torch, dev, args)
+    if args.copy_calibration:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        extra["copy_calibration_bytes"] = int(a.numel())
     out.update(extra)
     if not args.no_cpu_baseline:
-        rows = args.cpu_rows or min(wl.m, 4096)
+        rows = args.cpu_rows or wl.m
         out["cpu_baseline"] = cpu_baseline(wl, args.batch, xexact, y0[:rows].astype(np.float64), rows)
     print(json.dumps(out))
 
