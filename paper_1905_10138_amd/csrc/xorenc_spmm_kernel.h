@@ -295,134 +295,148 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const uint32_t *lut_g = lut + g;
   const uint32_t lane_id5 = (uint32_t)(rl * 2 + g);  // (row, half) as it appears in a patch entry
 
+  // table look-ups of one slice: S[rb][p] = sign half-word of this lane (before patches)
+  auto lookup = [&](const Comp &c, uint32_t(&S)[RB][Q]) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int p = 0; p < Q; ++p) {
+        uint32_t x;
+        if (two_dw)
+          x = __builtin_amdgcn_alignbit(c.e1[rb][p], c.e0[rb][p], e_shift);
+        else
+          x = c.e0[rb][p] >> e_shift;
+        uint32_t v;
+        if constexpr (NIBT == 1) {
+          v = lut_g[2 * (x & 255)];
+        } else if constexpr (NIBT == 2) {
+          const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+          v = t0 ^ t1;
+        } else if constexpr (NIBT == 3) {
+          const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+          const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))];
+          v = t0 ^ t1 ^ t2;
+        } else if constexpr (NIBT == 4) {
+          const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+          const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))], t3 = lut_g[2 * (768 + (x >> 24))];
+          v = t0 ^ t1 ^ t2 ^ t3;
+        } else {
+          v = lut_g[2 * (x & 255)];
+          if (nib > 1) v ^= lut_g[2 * (256 + ((x >> 8) & 255))];  // uniform branches
+          if (nib > 2) v ^= lut_g[2 * (512 + ((x >> 16) & 255))];
+          if (nib > 3) v ^= lut_g[2 * (768 + (x >> 24))];
+        }
+        S[rb][p] = v;
+      }
+  };
+  // B operands of MFMA step t of the slice currently in LDS
+  auto read_bfrag = [&](int t, bf16x8(&bf)[NCB]) {
+    const int par = t >> 1, h = t & 1;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
+      const s16x4 lo = lds_read_tr16(src);            // operand slots 0..3
+      const s16x4 hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
+      bf[cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
+
+  // Software pipeline of one wave.  While slice s is multiplied, slice s+1 moves registers -> LDS ->
+  // operand registers (each operand set is refilled as soon as its MFMAs have been issued), the
+  // table look-ups of slice s+1 are started, and the global loads of slice s+2 are issued.
   auto main_loop = [&](auto pf_tag) {
     constexpr bool PF = decltype(pf_tag)::value;
+    if (cnt <= 0) return;
     uint32_t pcur[RB][Q];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int p = 0; p < Q; ++p) pcur[rb][p] = 0u;
-    // LDS holds the X rows of the slice about to be consumed, xr those of the one after it, and
-    // the loads of the slice after that are issued as soon as xr has been copied to LDS.
+    bf16x8 bfrag[4][NCB];
+    uint32_t Snext[RB][Q];
     if constexpr (PRO2) {
-      if (cnt > 0) store_x(xr0);
+      store_x(xr0);
     } else {
-      if (cnt > 0) store_x(xr);
+      store_x(xr);
       if (cnt > 1) load_x(w0 + 1, xr);
     }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t]);
+    lookup(ring[0], Snext);
+
     for (int sb = w0; sb < w1; sb += 2) {
 #pragma unroll
       for (int d = 0; d < 2; ++d) {
         const int s = sb + d;
         if (s >= w1) break;  // uniform
-        const Comp cur = ring[d];
-        // decrypt: table look-ups first (LDS latency overlaps the operand reads below)
-        uint32_t Sx[RB][Q];
+        const bool has_next = s + 1 < w1;
+        uint32_t mw[RB];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) mw[rb] = ring[d].mw[rb];
+        // patch flips, then interleave sign and mask bits
+        uint32_t Iw[RB][Q][2];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int p = 0; p < Q; ++p) {
-            uint32_t x;
-            if (two_dw)
-              x = __builtin_amdgcn_alignbit(cur.e1[rb][p], cur.e0[rb][p], e_shift);
-            else
-              x = cur.e0[rb][p] >> e_shift;
-            uint32_t S;
-            if constexpr (NIBT == 1) {
-              S = lut_g[2 * (x & 255)];
-            } else if constexpr (NIBT == 2) {
-              const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
-              S = t0 ^ t1;
-            } else if constexpr (NIBT == 3) {
-              const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
-              const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))];
-              S = t0 ^ t1 ^ t2;
-            } else if constexpr (NIBT == 4) {
-              const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
-              const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))], t3 = lut_g[2 * (768 + (x >> 24))];
-              S = t0 ^ t1 ^ t2 ^ t3;
+            uint32_t S = Snext[rb][p];
+            if constexpr (PF) {
+              const uint32_t pe = __builtin_amdgcn_readlane(offrel[rb][p], s - w0 + 1);
+              for (uint32_t j = pcur[rb][p]; j < pe; ++j) {
+                const uint32_t v = __builtin_amdgcn_readlane(entv[rb][p], j);
+                if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
+              }
+              pcur[rb][p] = pe;
             } else {
-              S = lut_g[2 * (x & 255)];
-              if (nib > 1) S ^= lut_g[2 * (256 + ((x >> 8) & 255))];  // uniform branches
-              if (nib > 2) S ^= lut_g[2 * (512 + ((x >> 16) & 255))];
-              if (nib > 3) S ^= lut_g[2 * (768 + (x >> 24))];
-            }
-            Sx[rb][p] = S;
-          }
-        // The B operands are pulled into registers GS steps at a time; once the last group is
-        // out of LDS the buffer is free for the next slice, whose global loads are then re-armed.
-        constexpr int GS = (NCB >= 3) ? 1 : 4 / NCB;
-        uint32_t Iw[RB][Q][2];
-#pragma unroll
-        for (int t0 = 0; t0 < 4; t0 += GS) {
-          bf16x8 bfrag[GS][NCB];
-#pragma unroll
-          for (int tt = 0; tt < GS; ++tt) {
-            const int t = t0 + tt, par = t >> 1, h = t & 1;
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-              const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
-              const s16x4 lo = lds_read_tr16(src);            // operand slots 0..3
-              const s16x4 hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
-              bfrag[tt][cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-          }
-          if (t0 + GS == 4) {
-            if (s + 1 < w1) store_x(xr);  // LDS ops of a wave execute in order: the reads above are done
-            if (s + 2 < w1) {             // refill
-              load_comp(s + 2, ring[d]);
-              load_x(s + 2, xr);
-            }
-          }
-          if (t0 == 0) {
-            // patch flips, then interleave sign and mask bits
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-              for (int p = 0; p < Q; ++p) {
-                uint32_t S = Sx[rb][p];
-                if constexpr (PF) {
-                  const uint32_t pe = __builtin_amdgcn_readlane(offrel[rb][p], s - w0 + 1);
-                  for (uint32_t j = pcur[rb][p]; j < pe; ++j) {
-                    const uint32_t v = __builtin_amdgcn_readlane(entv[rb][p], j);
-                    if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
-                  }
-                  pcur[rb][p] = pe;
-                } else {
-                  const int rbg = blockIdx.x * RB + rb;
-                  if (rbg < L.nrb) {
-                    const int64_t u = (int64_t)p * L.n_units + (int64_t)rbg * L.spr + s;
-                    const uint32_t pa = __builtin_amdgcn_readfirstlane(L.patch_off[u]);
-                    const uint32_t pe = __builtin_amdgcn_readfirstlane(L.patch_off[u + 1]);
-                    for (uint32_t j = pa; j < pe; ++j) {
-                      const uint32_t v = L.patch[j];
-                      if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
-                    }
-                  }
+              const int rbg = blockIdx.x * RB + rb;
+              if (rbg < L.nrb) {
+                const int64_t u = (int64_t)p * L.n_units + (int64_t)rbg * L.spr + s;
+                const uint32_t pa = __builtin_amdgcn_readfirstlane(L.patch_off[u]);
+                const uint32_t pe = __builtin_amdgcn_readfirstlane(L.patch_off[u + 1]);
+                for (uint32_t j = pa; j < pe; ++j) {
+                  const uint32_t v = L.patch[j];
+                  if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
                 }
-                const uint32_t mw = cur.mw[rb];
-                Iw[rb][p][0] = (mw & 0x55555555u) | ((S << 1) & 0xAAAAAAAAu);
-                Iw[rb][p][1] = ((mw >> 1) & 0x55555555u) | (S & 0xAAAAAAAAu);
               }
+            }
+            Iw[rb][p][0] = (mw[rb] & 0x55555555u) | ((S << 1) & 0xAAAAAAAAu);
+            Iw[rb][p][1] = ((mw[rb] >> 1) & 0x55555555u) | (S & 0xAAAAAAAAu);
           }
+        auto mfma_step = [&](int t) {
+          const int par = t >> 1, h = t & 1;
 #pragma unroll
-          for (int tt = 0; tt < GS; ++tt) {
-            const int t = t0 + tt, par = t >> 1, h = t & 1;
+          for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
+            for (int p = 0; p < Q; ++p) {
+              const uint32_t I = Iw[rb][p][par];
+              u32x4 a;
 #pragma unroll
-              for (int p = 0; p < Q; ++p) {
-                const uint32_t I = Iw[rb][p][par];
-                u32x4 a;
+              for (int dd = 0; dd < 4; ++dd) a[dd] = (I << (14 - 2 * (4 * h + dd))) & 0xC000C000u;
+              const bf16x8 afrag = __builtin_bit_cast(bf16x8, a);
 #pragma unroll
-                for (int dd = 0; dd < 4; ++dd) a[dd] = (I << (14 - 2 * (4 * h + dd))) & 0xC000C000u;
-                const bf16x8 afrag = __builtin_bit_cast(bf16x8, a);
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb)
-                  acc[p][rb][cb] =
-                      __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[tt][cb], acc[p][rb][cb], 0, 0, 0);
-              }
-          }
+              for (int cb = 0; cb < NCB; ++cb)
+                acc[p][rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[t][cb], acc[p][rb][cb], 0, 0, 0);
+            }
+        };
+        mfma_step(0);
+        mfma_step(1);
+        // all operands of slice s are in registers: the LDS buffer takes slice s+1, whose operand
+        // reads follow in program order (LDS ops of one wave execute in order)
+        if (has_next) store_x(xr);
+        if (s + 2 < w1) {
+          load_comp(s + 2, ring[d]);
+          load_x(s + 2, xr);
+        }
+        if (has_next) {
+          read_bfrag(0, bfrag[0]);
+          read_bfrag(1, bfrag[1]);
+        }
+        mfma_step(2);
+        if (has_next) read_bfrag(2, bfrag[2]);
+        mfma_step(3);
+        if (has_next) {
+          read_bfrag(3, bfrag[3]);
+          lookup(ring[d ^ 1], Snext);
         }
       }
     }
@@ -562,8 +576,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
   const int blocks = (B + 31) / 32;
   if constexpr (Q == 1) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
-    if (blocks == 2) return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
-    return launch_spmm<4, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);
