@@ -64,29 +64,49 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   constexpr int EPC = XF32 ? 4 : 8;            // X elements per chunk
   constexpr int ESZ = XF32 ? 4 : 2;            // bytes per X element
   constexpr int NIBMAX = NIBT ? NIBT : 4;
-  constexpr int TS = CW + 8;                   // row stride (floats) of a reduction tile
-  constexpr int TILE = ROWS * TS;
-  constexpr int FIT = (NW * XBUF) / (TILE * 4);
+  constexpr int TS = ROWS + 4;                 // stride (floats) between columns of a reduction tile
+  constexpr int TILE = CW * TS;                // a tile is stored column-major: [column][row]
+  // The epilogue gives every wave its own reduction tile when NW tiles fit in LDS next to the
+  // tables (one round); otherwise the tiles live in the X buffers and are reused over rounds.
+  constexpr bool ONE_ROUND = NW * TILE * 4 <= 148 * 1024;
+  constexpr int FIT = ONE_ROUND ? NW : (NW * XBUF) / (TILE * 4);
   constexpr int NREG = FIT >= 8 ? (NW < 8 ? NW : 8) : (FIT >= 4 ? 4 : (FIT >= 2 ? 2 : 1));
+  constexpr int LDSB = (NW * XBUF > NREG * TILE * 4) ? NW * XBUF : NREG * TILE * 4;
   static_assert(!XF32 || NCB % 3 == 0, "fp32 X uses three bf16 terms per column");
   static_assert(FIT >= 1, "a reduction tile must fit in the X buffers");
   static_assert(NW % NREG == 0, "waves must split evenly over the reduction tiles");
-  __shared__ __attribute__((aligned(16))) uint8_t xbuf_all[NW * XBUF];
-  __shared__ uint32_t lut[NIBMAX * 512];
+  __shared__ __attribute__((aligned(16))) uint8_t xbuf_all[LDSB];
+  // Small tables are kept once per wave (no workgroup barrier before the first look-up); larger
+  // ones are shared by the workgroup.
+  constexpr bool PRIV_LUT = NIBT >= 1 && LDSB + NW * NIBT * 2048 + Q * ROWS * 4 <= 160 * 1024;
+  __shared__ uint32_t lut_all[(PRIV_LUT ? NW : 1) * NIBMAX * 512];
+  uint32_t *const lut = lut_all + (PRIV_LUT ? (threadIdx.x >> 6) * NIBMAX * 512 : 0);
   __shared__ __attribute__((aligned(16))) float alpha_s[Q * ROWS];
 
+  // Every kernel argument the kernel uses is fetched up front in one batch of scalar loads (one
+  // round trip to the argument segment instead of one per first use).
+  const uint8_t *const l_enc = L.enc;
+  const uint32_t *const l_mask32 = L.mask32;
+  const uint32_t *const l_patch_off = L.patch_off;
+  const uint16_t *const l_patch = L.patch;
+  const float *const l_alpha = L.alpha;
+  const int l_m = L.m, l_n = L.n, l_spr = L.spr, l_nrb = L.nrb, l_n_units = L.n_units, l_nib = L.nib, l_q = L.q;
+  const int64_t l_n_slots = L.n_slots;
+  asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
+               "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_nib), "s"(l_q), "s"(l_n_slots), "s"(Xv), "s"(ldx), "s"(B),
+               "s"(Y), "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, rl = lane & 31;
   const int row0 = blockIdx.x * ROWS;
   const int col0 = blockIdx.y * NR;  // first real X column of this workgroup
-  const int nib = NIBT ? NIBT : L.nib;
+  const int nib = NIBT ? NIBT : l_nib;
   uint8_t *xbuf = xbuf_all + wave * XBUF;
 
   // ---- this wave's contiguous slice range [w0, w1) inside the workgroup's [s_begin, s_end)
   const int s_begin = blockIdx.z * slices_per_split;
-  const int s_end = min(L.spr, s_begin + slices_per_split);
+  const int s_end = min(l_spr, s_begin + slices_per_split);
   const int per_wave = (s_end - s_begin + NW - 1) / NW;
   const int w0 = min(s_end, s_begin + wave * per_wave);
   const int w1 = min(s_end, w0 + per_wave);
@@ -94,13 +114,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 
   // ---- buffer descriptors
   const int64_t row_bytes = ldx * ESZ;
-  const uint32_t x_extent = (uint32_t)((int64_t)(L.n - 1) * row_bytes + (int64_t)(B - col0) * ESZ);
+  const uint32_t x_extent = (uint32_t)((int64_t)(l_n - 1) * row_bytes + (int64_t)(B - col0) * ESZ);
   const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t *>(static_cast<const uint8_t *>(Xv) + (int64_t)col0 * ESZ), 0, x_extent, kRsrcFlags);
   const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint32_t *>(L.mask32), 0, (uint32_t)(L.n_slots * 8), kRsrcFlags);
+      const_cast<uint32_t *>(l_mask32), 0, (uint32_t)(l_n_slots * 8), kRsrcFlags);
   const __amdgpu_buffer_rsrc_t ersrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t *>(L.enc), 0, (uint32_t)(L.n_slots * L.q * nib), kRsrcFlags);
+      const_cast<uint8_t *>(l_enc), 0, (uint32_t)(l_n_slots * l_q * nib), kRsrcFlags);
 
   // ---- X loader.  One slice = 64 rows of X.  Chunk = 16 bytes of a row (8 bf16 / 4 fp32 columns).
   // XFAST: chunk i of a lane is (row i*RPI + lane/NCH, chunk lane%NCH), 16-byte loads.
@@ -109,7 +129,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   // padded X columns only reaches output columns that are never stored.
   // Register-light variants fetch the first two slices at once; the others fetch the second
   // slice only after the first has been copied to LDS.
-  constexpr bool PRO2 = (NCH <= 8) && !XF32;
+  constexpr bool PRO2 = (NCH <= 8) && !XF32 && NW <= 8;
   uint4 xr[NCH];                // X rows of the slice after the one in LDS
   uint4 xr0[PRO2 ? NCH : 1];    // prologue only: X rows of the first slice
   const int xrow = XFAST ? lane / NCH : lane;
@@ -200,12 +220,12 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       c.mw[rb] = 0u;
 #pragma unroll
       for (int p = 0; p < Q; ++p) c.e0[rb][p] = c.e1[rb][p] = 0u;
-      if (rbg < L.nrb) {  // uniform
-        const uint32_t u = (uint32_t)(rbg * L.spr + s);  // uniform
+      if (rbg < l_nrb) {  // uniform
+        const uint32_t u = (uint32_t)(rbg * l_spr + s);  // uniform
         c.mw[rb] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_lane_off, u * 256u, 0);
 #pragma unroll
         for (int p = 0; p < Q; ++p) {
-          const uint32_t so = ((uint32_t)p * (uint32_t)L.n_slots + u * 32u) * (uint32_t)nib;
+          const uint32_t so = ((uint32_t)p * (uint32_t)l_n_slots + u * 32u) * (uint32_t)nib;
           c.e0[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so, 0);
           if (two_dw) c.e1[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so + 4u, 0);
         }
@@ -235,31 +255,50 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
     for (int p = 0; p < Q; ++p) {
       offv[rb][p] = 0u;
-      if (rbg < L.nrb && pre_ok && cnt > 0) {
-        const uint32_t *po = L.patch_off + ((int64_t)p * L.n_units + (int64_t)rbg * L.spr + w0);
+      if (rbg < l_nrb && pre_ok && cnt > 0) {
+        const uint32_t *po = l_patch_off + ((int64_t)p * l_n_units + (int64_t)rbg * l_spr + w0);
         if (lane <= cnt) offv[rb][p] = po[lane];
       }
     }
   }
 
   // ---- XOR tables T_b[v] = XOR of the columns 8b..8b+7 of M selected by the bits of v, and alpha
-  for (int b = 0; b < nib; ++b)  // uniform
-    for (int v = tid; v < 256; v += NW * 64) {
+  if constexpr (PRIV_LUT) {
+    // each lane builds entries lane, lane+64, lane+128, lane+192 of its wave's copy
+    for (int b = 0; b < NIBT; ++b) {
       uint32_t lo = 0, hi = 0;
 #pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if ((v >> t) & 1) {
+      for (int t = 0; t < 6; ++t)
+        if ((lane >> t) & 1) {
           lo ^= L.Mcol_lo[8 * b + t];
           hi ^= L.Mcol_hi[8 * b + t];
         }
-      lut[2 * (b * 256 + v)] = lo;
-      lut[2 * (b * 256 + v) + 1] = hi;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t klo = ((k & 1) ? L.Mcol_lo[8 * b + 6] : 0u) ^ ((k & 2) ? L.Mcol_lo[8 * b + 7] : 0u);
+        const uint32_t khi = ((k & 1) ? L.Mcol_hi[8 * b + 6] : 0u) ^ ((k & 2) ? L.Mcol_hi[8 * b + 7] : 0u);
+        *reinterpret_cast<uint2 *>(lut + 2 * (b * 256 + 64 * k + lane)) = make_uint2(lo ^ klo, hi ^ khi);
+      }
     }
-  for (int i = tid; i < Q * ROWS; i += NW * 64) {
-    const int p = i / ROWS, r = row0 + i % ROWS;
-    alpha_s[i] = (r < L.m) ? -0.5f * L.alpha[(int64_t)p * L.m + r] : 0.f;
+  } else {
+    for (int b = 0; b < nib; ++b)  // uniform
+      for (int v = tid; v < 256; v += NW * 64) {
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+          if ((v >> t) & 1) {
+            lo ^= L.Mcol_lo[8 * b + t];
+            hi ^= L.Mcol_hi[8 * b + t];
+          }
+        lut[2 * (b * 256 + v)] = lo;
+        lut[2 * (b * 256 + v) + 1] = hi;
+      }
   }
-  __syncthreads();
+  for (int i = tid; i < Q * ROWS; i += NW * 64) {  // read only after the barrier that follows the loop
+    const int p = i / ROWS, r = row0 + i % ROWS;
+    alpha_s[i] = (r < l_m) ? -0.5f * l_alpha[(int64_t)p * l_m + r] : 0.f;
+  }
+  if constexpr (!PRIV_LUT) __syncthreads();
 
   // ---- patch entries of the range: lane j holds the j-th entry (relative to the range start).
   // A range with more than 63 units or more than 64 entries of one (row block, plane) reads its
@@ -275,7 +314,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       offrel[rb][p] = offv[rb][p] - base;
       entv[rb][p] = 0u;
       if (total > 64u) pfast = false;
-      if ((uint32_t)lane < min(total, 64u)) entv[rb][p] = (L.patch + base)[lane];
+      if ((uint32_t)lane < min(total, 64u)) entv[rb][p] = (l_patch + base)[lane];
     }
 
   f32x16 acc[Q][RB][NCB];
@@ -370,6 +409,12 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
         const int s = sb + d;
         if (s >= w1) break;  // uniform
         const bool has_next = s + 1 < w1;
+        // the two waves that share a SIMD take turns at the higher issue priority so that neither
+        // falls behind (arbitration otherwise favours the older wave for the whole kernel)
+        if (((wave >> 2) & 1) == d)
+          __builtin_amdgcn_s_setprio(1);
+        else
+          __builtin_amdgcn_s_setprio(0);
         uint32_t mw[RB];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) mw[rb] = ring[d].mw[rb];
@@ -389,12 +434,12 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
               pcur[rb][p] = pe;
             } else {
               const int rbg = blockIdx.x * RB + rb;
-              if (rbg < L.nrb) {
-                const int64_t u = (int64_t)p * L.n_units + (int64_t)rbg * L.spr + s;
-                const uint32_t pa = __builtin_amdgcn_readfirstlane(L.patch_off[u]);
-                const uint32_t pe = __builtin_amdgcn_readfirstlane(L.patch_off[u + 1]);
+              if (rbg < l_nrb) {
+                const int64_t u = (int64_t)p * l_n_units + (int64_t)rbg * l_spr + s;
+                const uint32_t pa = __builtin_amdgcn_readfirstlane(l_patch_off[u]);
+                const uint32_t pe = __builtin_amdgcn_readfirstlane(l_patch_off[u + 1]);
                 for (uint32_t j = pa; j < pe; ++j) {
-                  const uint32_t v = L.patch[j];
+                  const uint32_t v = l_patch[j];
                   if ((v >> 5) == lane_id5) S ^= 1u << (v & 31);
                 }
               }
@@ -447,7 +492,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     main_loop(BoolC<false>{});
 
   // ---- epilogue: scale by alpha (fp32) and reduce the waves in a fixed order.  NREG tiles of
-  // ROWS x TS floats live in the (now idle) X buffers; wave w adds into tile w % NREG in round
+  // CW x TS floats (column-major) live in LDS over the (now idle) X buffers; wave w adds into tile w % NREG in round
   // w / NREG, then every thread sums the NREG tiles of its outputs in ascending tile order.
   // acc element i of a lane is row 8*(i/4) + 4*g + i%4, column rl of its 32x32 block.
 #pragma unroll
@@ -478,38 +523,48 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            float *dst = tile + (rb * 32 + 8 * (i >> 2) + 4 * g + (i & 3)) * TS + cb * 32 + rl;
-            if (round == 0)
-              *dst = acc[0][rb][cb][i];
-            else
-              *dst += acc[0][rb][cb][i];
+          for (int j4 = 0; j4 < 4; ++j4) {
+            // four consecutive rows of one column: one 16-byte LDS access
+            f32x4 *dst = reinterpret_cast<f32x4 *>(tile + (cb * 32 + rl) * TS + rb * 32 + 8 * j4 + 4 * g);
+            f32x4 v = {acc[0][rb][cb][4 * j4], acc[0][rb][cb][4 * j4 + 1], acc[0][rb][cb][4 * j4 + 2],
+                       acc[0][rb][cb][4 * j4 + 3]};
+            if (round != 0) v += *dst;
+            *dst = v;
           }
     }
     __syncthreads();
   }
-  auto reduced = [&](int off) {
-    float v = red[off];
+  // final pass: a thread owns four consecutive rows of one column; lanes run over columns, so each
+  // of its four stores is contiguous across the wave
+  auto reduced4 = [&](int col, int rq) {
+    const float *src = red + col * TS + 4 * rq;
+    f32x4 v = *reinterpret_cast<const f32x4 *>(src);
 #pragma unroll
-    for (int r = 1; r < NREG; ++r) v += red[r * TILE + off];
+    for (int r = 1; r < NREG; ++r) v += *reinterpret_cast<const f32x4 *>(src + r * TILE);
     return v;
   };
-  for (int idx = tid; idx < ROWS * NR; idx += NW * 64) {
-    const int row = idx / NR, nn = idx % NR;
-    const int gr = row0 + row, gc = col0 + nn;
-    if (gr < L.m && gc < B) {
-      float v;
+  for (int idx = tid; idx < (ROWS / 4) * NR; idx += NW * 64) {
+    const int rq = idx / NR, nn = idx % NR;
+    const int gc = col0 + nn;
+    if (gc < B) {
+      f32x4 v;
       if (XF32) {
-        const int o = row * TS + 96 * (nn >> 5) + (nn & 31);
-        v = (reduced(o) + reduced(o + 32)) + reduced(o + 64);
+        const int c = 96 * (nn >> 5) + (nn & 31);
+        v = (reduced4(c, rq) + reduced4(c + 32, rq)) + reduced4(c + 64, rq);
       } else {
-        v = reduced(row * TS + nn);
+        v = reduced4(nn, rq);
       }
-      float *dst = Y + (int64_t)gr * ldy + gc;
-      if (use_atomic)
-        unsafeAtomicAdd(dst, v);
-      else
-        *dst = v;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int gr = row0 + 4 * rq + k;
+        if (gr < l_m) {
+          float *dst = Y + (int64_t)gr * ldy + gc;
+          if (use_atomic)
+            unsafeAtomicAdd(dst, v[k]);
+          else
+            *dst = v[k];
+        }
+      }
     }
   }
 }
@@ -575,7 +630,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
   }
   const int blocks = (B + 31) / 32;
   if constexpr (Q == 1) {
-    if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (blocks == 1) return launch_spmm<1, Q, 2, false, 16>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
