@@ -55,8 +55,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
                                                       int use_atomic) {
   constexpr int CW = 32 * NCB;                 // bf16 columns held in LDS per X row
-  constexpr int RSB = CW * 2 + 16;             // LDS row stride in bytes (16 bytes of padding)
-  constexpr int XBUF = 64 * RSB;               // one wave's buffer: the 64 X rows of a slice
+  // XDIR: bf16 X with 16-byte aligned rows goes from global memory straight into LDS (no register
+  // staging); the wave then owns two unpadded, swizzled slice buffers.  Otherwise X passes through
+  // registers into one padded buffer.
+  constexpr bool XDIR = XFAST && !XF32;
+  constexpr int RSB = XDIR ? CW * 2 : CW * 2 + 16;  // LDS row stride in bytes
+  constexpr int XSL = 64 * RSB;                     // the 64 X rows of one slice
+  constexpr int XBUF = XDIR ? 2 * XSL : XSL;        // one wave's LDS share
   constexpr int ROWS = 32 * RB;
   constexpr int NR = XF32 ? CW / 3 : CW;       // real X columns per workgroup
   constexpr int NCH = XF32 ? NR / 4 : CW / 8;  // 16-byte chunks per X row in global memory
@@ -132,10 +137,38 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   constexpr bool PRO2 = (NCH <= 8) && !XF32 && NW <= 8;
   uint4 xr[NCH];                // X rows of the slice after the one in LDS
   uint4 xr0[PRO2 ? NCH : 1];    // prologue only: X rows of the first slice
-  const int xrow = XFAST ? lane / NCH : lane;
-  const int xch = XFAST ? lane % NCH : 0;
+  // XDIR layout of a slice buffer: X row r sits at row position pos(r), whose bits 0..5 are bits
+  // 1,4,0,2,3,5 of r, and 16-byte chunk c of that row at chunk c ^ swz(pos), swz = (pos&3)<<1 for
+  // 8-chunk rows and ((pos>>1)&1)<<1 for 4-chunk rows.  The four X rows one transposing read
+  // touches (r, r+2, r+16, r+18) are then four consecutive positions whose 32-byte pieces fall
+  // into four different groups of eight banks.  A direct load writes lane l's 16 bytes at
+  // (instruction base) + 16 l, so lane l fetches the chunk that belongs there.
+  constexpr int LB = (RPI == 8) ? 3 : 4;  // position bits supplied by the lane (XDIR)
+  auto row_of_pos = [](int pos) {
+    return ((pos & 1) << 1) | (((pos >> 1) & 1) << 4) | ((pos >> 2) & 1) | (((pos >> 3) & 1) << 2) |
+           (((pos >> 4) & 1) << 3) | (((pos >> 5) & 1) << 5);
+  };
+  auto swz_of_pos = [](int pos) { return (NCH == 8) ? ((pos & 3) << 1) : (((pos >> 1) & 1) << 1); };
+  const int xrow = XDIR ? row_of_pos(lane / NCH) : (XFAST ? lane / NCH : lane);
+  const int xch = XDIR ? ((lane % NCH) ^ swz_of_pos(lane / NCH)) : (XFAST ? lane % NCH : 0);
   const uint32_t x_lane_off = (uint32_t)(xrow * row_bytes) + ((col0 + xch * EPC < B) ? xch * 16 : 0);
   const uint32_t x_lds_off = XFAST ? (uint32_t)(xrow * RSB + xch * 16) : (uint32_t)(lane * RSB);
+  // direct global -> LDS copy of slice s into slice buffer `which` of this wave (XDIR)
+  const uint64_t x_base = reinterpret_cast<uint64_t>(static_cast<const uint8_t *>(Xv) + (int64_t)col0 * ESZ);
+  const u32x4 xdesc = {(uint32_t)x_base, (uint32_t)(x_base >> 32) & 0xffffu, x_extent, kRsrcFlags};
+  const uint32_t xbuf_lds = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t *)(xbuf));
+  auto dma_x = [&](int s, int which) {
+    const uint32_t sbase = (uint32_t)(s * 64 * row_bytes);  // uniform
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const uint32_t so = sbase + (uint32_t)(row_of_pos(i << LB) * row_bytes);
+      const uint32_t dst = xbuf_lds + (uint32_t)(which * XSL + i * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(x_lane_off),
+                   "s"(xdesc), "s"(so)
+                   : "memory");
+    }
+  };
   auto load_x = [&](int s, uint4(&xr)[NCH]) {
     const uint32_t sbase = (uint32_t)(s * 64 * row_bytes);  // uniform
     if constexpr (XFAST) {
@@ -233,18 +266,79 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     }
   };
 
+  // XDIR: the same loads written as assembly, unconditional (a row block beyond the matrix reads
+  // a zero mask through the descriptor's range check, which makes its operand +-0 whatever the
+  // encrypted bits are).  With every load of the loop hidden from the compiler, the loop's only
+  // waits on memory are the explicit ones below.
+  const u32x4 mdesc = {(uint32_t)reinterpret_cast<uint64_t>(l_mask32),
+                       (uint32_t)(reinterpret_cast<uint64_t>(l_mask32) >> 32) & 0xffffu, (uint32_t)(l_n_slots * 8),
+                       kRsrcFlags};
+  const u32x4 edesc = {(uint32_t)reinterpret_cast<uint64_t>(l_enc),
+                       (uint32_t)(reinterpret_cast<uint64_t>(l_enc) >> 32) & 0xffffu,
+                       (uint32_t)(l_n_slots * l_q * nib), kRsrcFlags};
+  auto load_comp_hidden = [&](int s, Comp &c) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const uint32_t u = (uint32_t)((blockIdx.x * RB + rb) * l_spr + s);  // uniform
+      asm volatile("buffer_load_dword %0, %1, %2, %3 offen"
+                   : "=&v"(c.mw[rb])
+                   : "v"(m_lane_off), "s"(mdesc), "s"(u * 256u)
+                   : "memory");
+#pragma unroll
+      for (int p = 0; p < Q; ++p) {
+        const uint32_t so = ((uint32_t)p * (uint32_t)l_n_slots + u * 32u) * (uint32_t)nib;
+        asm volatile("buffer_load_dword %0, %1, %2, %3 offen"
+                     : "=&v"(c.e0[rb][p])
+                     : "v"(e_lane_off), "s"(edesc), "s"(so)
+                     : "memory");
+        if (two_dw)
+          asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:4"
+                       : "=&v"(c.e1[rb][p])
+                       : "v"(e_lane_off), "s"(edesc), "s"(so)
+                       : "memory");
+        else
+          c.e1[rb][p] = 0u;
+      }
+    }
+  };
+  // every outstanding load of this wave has returned; the registers the hidden loads filled may be
+  // read from here on
+  auto wait_loads = [&](Comp &c) {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      asm volatile("" : "+v"(c.mw[rb]));
+#pragma unroll
+      for (int p = 0; p < Q; ++p) {
+        asm volatile("" : "+v"(c.e0[rb][p]));
+        asm volatile("" : "+v"(c.e1[rb][p]));
+      }
+    }
+  };
+
   // ---- first loads go out before anything else so that they overlap the table build
   Comp ring[2];
-  if (cnt > 0) {
-    load_comp(w0, ring[0]);
-    if constexpr (PRO2)
-      load_x(w0, xr0);
-    else
-      load_x(w0, xr);
-  }
-  if (cnt > 1) {
-    load_comp(w0 + 1, ring[1]);
-    if constexpr (PRO2) load_x(w0 + 1, xr);
+  if constexpr (XDIR) {
+    if (cnt > 0) {
+      load_comp_hidden(w0, ring[0]);
+      dma_x(w0, 0);
+    }
+    if (cnt > 1) {
+      load_comp_hidden(w0 + 1, ring[1]);
+      dma_x(w0 + 1, 1);
+    }
+  } else {
+    if (cnt > 0) {
+      load_comp(w0, ring[0]);
+      if constexpr (PRO2)
+        load_x(w0, xr0);
+      else
+        load_x(w0, xr);
+    }
+    if (cnt > 1) {
+      load_comp(w0 + 1, ring[1]);
+      if constexpr (PRO2) load_x(w0 + 1, xr);
+    }
   }
   // patch offsets of the whole range: lane i holds the offset of unit i of the range
   const bool pre_ok = cnt <= 63;  // uniform
@@ -331,6 +425,16 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const int jj = (lane >> 2) & 3, c4 = lane & 3;
   const uint8_t *tr_ptr =
       xbuf + (32 * g + 2 * (jj >> 1) + 16 * (jj & 1)) * RSB + (16 * ((lane >> 4) & 1) + 4 * c4) * 2;
+  // XDIR: byte offset of this lane's 8 bytes inside a slice buffer, per column block
+  uint32_t tr_off[NCB];
+  {
+    const int pos_lane = (jj >> 1) | ((jj & 1) << 1) | (g << 5);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      const int c = 4 * cb + 2 * ((lane >> 4) & 1) + (c4 >> 1);
+      tr_off[cb] = (uint32_t)(pos_lane * RSB + ((c ^ swz_of_pos(pos_lane)) * 16) + 8 * (c4 & 1));
+    }
+  }
   const uint32_t *lut_g = lut + g;
   const uint32_t lane_id5 = (uint32_t)(rl * 2 + g);  // (row, half) as it appears in a patch entry
 
@@ -369,13 +473,21 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       }
   };
   // B operands of MFMA step t of the slice currently in LDS
-  auto read_bfrag = [&](int t, bf16x8(&bf)[NCB]) {
+  auto read_bfrag = [&](int t, bf16x8(&bf)[NCB], int which) {
     const int par = t >> 1, h = t & 1;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
-      const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
-      const s16x4 lo = lds_read_tr16(src);            // operand slots 0..3
-      const s16x4 hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
+      s16x4 lo, hi;
+      if constexpr (XDIR) {
+        // X rows +par, +8h, +4 are row positions +4, +16, +8
+        const uint8_t *src = xbuf + which * XSL + tr_off[cb] + (4 * par + 16 * h) * RSB;
+        lo = lds_read_tr16(src);
+        hi = lds_read_tr16(src + 8 * RSB);
+      } else {
+        const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
+        lo = lds_read_tr16(src);            // operand slots 0..3
+        hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
+      }
       bf[cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
   };
@@ -393,14 +505,26 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       for (int p = 0; p < Q; ++p) pcur[rb][p] = 0u;
     bf16x8 bfrag[4][NCB];
     uint32_t Snext[RB][Q];
-    if constexpr (PRO2) {
+    if constexpr (XDIR) {
+      // both prologue slices have landed in LDS, their compressed words in registers
+      wait_loads(ring[0]);
+      if (cnt > 1) wait_loads(ring[1]);
+      // the compiler places its own wait for the patch words here, not at their first use in the loop
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int p = 0; p < Q; ++p) {
+          asm volatile("" : "+v"(offrel[rb][p]));
+          asm volatile("" : "+v"(entv[rb][p]));
+        }
+    } else if constexpr (PRO2) {
       store_x(xr0);
     } else {
       store_x(xr);
       if (cnt > 1) load_x(w0 + 1, xr);
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t]);
+    for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t], 0);
     lookup(ring[0], Snext);
 
     for (int sb = w0; sb < w1; sb += 2) {
@@ -467,20 +591,33 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
         mfma_step(1);
         // all operands of slice s are in registers: the LDS buffer takes slice s+1, whose operand
         // reads follow in program order (LDS ops of one wave execute in order)
-        if (has_next) store_x(xr);
-        if (s + 2 < w1) {
-          load_comp(s + 2, ring[d]);
-          load_x(s + 2, xr);
+        if constexpr (XDIR) {
+          // slice s+1 was requested one iteration ago: wait for it.  Slice buffer d (slice s) has no
+          // reader left -- its last operand read fed the look-up wait at the top of this iteration --
+          // so slice s+2 may start to land in it.
+          __builtin_amdgcn_sched_barrier(0);
+          wait_loads(ring[d ^ 1]);
+          if (s + 2 < w1) {
+            dma_x(s + 2, d);
+            load_comp_hidden(s + 2, ring[d]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        } else {
+          if (has_next) store_x(xr);
+          if (s + 2 < w1) {
+            load_comp(s + 2, ring[d]);
+            load_x(s + 2, xr);
+          }
         }
         if (has_next) {
-          read_bfrag(0, bfrag[0]);
-          read_bfrag(1, bfrag[1]);
+          read_bfrag(0, bfrag[0], d ^ 1);
+          read_bfrag(1, bfrag[1], d ^ 1);
         }
         mfma_step(2);
-        if (has_next) read_bfrag(2, bfrag[2]);
+        if (has_next) read_bfrag(2, bfrag[2], d ^ 1);
         mfma_step(3);
         if (has_next) {
-          read_bfrag(3, bfrag[3]);
+          read_bfrag(3, bfrag[3], d ^ 1);
           lookup(ring[d ^ 1], Snext);
         }
       }
@@ -605,7 +742,10 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
   const dim3 grid(row_groups, col_groups, ks);
   const int atomic = ks > 1 ? 1 : 0;
   if (!x_fast) {
-    launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+    if constexpr (RB <= 2)  // the larger tiles exist only for the aligned layout
+      launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+    else
+      return XORENC_EUNSUPPORTED;
   } else {
     switch (D.nib) {
       case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
@@ -631,6 +771,9 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
   const int blocks = (B + 31) / 32;
   if constexpr (Q == 1) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false, 16>(D, X, ldx, B, Y, ldy, x_fast, st);
+    // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
+    if (x_fast && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
+      return launch_spmm<2, Q, 4, false>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
