@@ -5,21 +5,25 @@
 // Operand synthesis.  The MFMA A operand is built in registers as bf16 values -2*t, t in
 // {-1,0,+1} the ternary weight of one bit-plane: bit 15 = quantised bit, bit 14 = mask bit, all
 // other bits 0 (0xC000 = -2, 0x4000 = +2, 0x0000 / 0x8000 = +-0).  The factor -1/2 is folded into
-// alpha in the fp32 epilogue, so the scales are never rounded to bf16.
+// alpha in the fp32 epilogue, so the scales are never rounded to bf16.  These patterns are what the
+// FP4 (e2m1) codes 1100, 0100, 0000, 1000 convert to, and gfx950 converts two codes to two bf16
+// values in one instruction: the (mask, sign) bit pairs are arranged as the top two bits of 4-bit
+// codes (two instructions per eight weights) and each operand dword then costs one conversion.
 //
 // Work decomposition.  A workgroup of NW waves owns RB row blocks of 32 rows and CW = 32*NCB
 // columns of X.  The waves split the reduction dimension into contiguous slice ranges and are
 // fully independent until the final reduction: each wave streams the 64 rows of X that belong to
-// its current slice through a private LDS buffer (global -> registers PD slices ahead, registers
-// -> LDS, LDS -> operand registers with the transposing LDS read), so the main loop has no
-// workgroup barrier.  Lane (rl = lane%32, g = lane/32) holds the 32-bit half g of the slice of
-// row rl of each row block.
+// its current slice through private LDS buffers and gathers its B operands from them with the
+// transposing LDS read, so the main loop has no workgroup barrier.  Aligned bf16 X goes from global
+// memory straight into LDS (two slice buffers per wave, requested a slice and a half ahead); any
+// other X passes through registers (one buffer).  Lane (rl = lane%32, g = lane/32) holds the
+// 32-bit half g of the slice of row rl of each row block.
 //
-// One 32-bit half feeds 4 MFMA steps t = 2*par + h.  With I_par the word whose bit pairs
-// (2a, 2a+1) hold (mask, sign) of half-word bit 2a+par, operand dword d of step t is
-// (I_par << (14 - 2*(4h+d))) & 0xC000C000: its low element is half-word bit 8h+2d+par, its high
-// element bit 8h+2d+par+16.  So operand slot j of step t of half g is the W column (X row)
-//     64 s + 32 g + 8 h + par + 2 (j>>1) + 16 (j&1)
+// One 32-bit half feeds 4 MFMA steps t = 2*par + e.  I_par is the word whose bit pairs
+// (2k, 2k+1) hold (mask, sign) of half-word bit 2k+par; code word (par, e) keeps the pairs with
+// k%2 = e, pair k in the top bits of code k/2.  Byte d of that word is operand dword d, so operand
+// slot j = 2d + (high code) of step t of half g is the W column (X row)
+//     64 s + 32 g + 8 (j>>1) + 4 (j&1) + 2 e + par
 // and the B operand is gathered from exactly those X rows.
 //
 // Addressing.  Every global load in the loop is a buffer load: (descriptor) + (per-lane 32-bit
@@ -44,12 +48,34 @@ __device__ inline s16x4 lds_read_tr16(const uint8_t *p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
 }
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// Eight FP4 (e2m1) codes -> eight bf16 values, one conversion per pair: code 0100 is +2, 1100 is -2,
+// 0000 / 1000 are +-0; byte d of w becomes operand dword d (low code in the low half).
+__device__ inline u32x4 expand_fp4_codes(uint32_t w) {
+  u32x4 a;
+  a[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, 1.0f, 0));
+  a[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, 1.0f, 1));
+  a[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, 1.0f, 2));
+  a[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, 1.0f, 3));
+  return a;
+}
+
+constexpr int largest_divisor_at_most(int n, int cap) {
+  int best = 1;
+  for (int d = 1; d <= n && d <= cap; ++d)
+    if (n % d == 0) best = d;
+  return best;
+}
+
 template <bool V>
 struct BoolC {
   static constexpr bool value = V;
 };
 
 // NIBT = n_in/8 known at compile time (1..4), or 0: read it from the layer at run time.
+// PD = slice buffers per wave on the direct path: 2 (loads a slice and a half ahead, two waves per
+// SIMD hide each other's waits) or 1 (loads one slice ahead, more waves per SIMD do the hiding).
 template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT>
 __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
@@ -61,7 +87,9 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   constexpr bool XDIR = XFAST && !XF32;
   constexpr int RSB = XDIR ? CW * 2 : CW * 2 + 16;  // LDS row stride in bytes
   constexpr int XSL = 64 * RSB;                     // the 64 X rows of one slice
-  constexpr int XBUF = XDIR ? 2 * XSL : XSL;        // one wave's LDS share
+  constexpr int KC = RB * (1 + Q * (NIBT == 3 ? 2 : 1));  // compressed dwords per lane and slice (XDIR)
+  constexpr int CSL = KC * 256;                           // their staging area for one slice (XDIR)
+  constexpr int XBUF = XDIR ? PD * (XSL + CSL) : XSL;     // one wave's LDS share (PD slice buffers)
   constexpr int ROWS = 32 * RB;
   constexpr int NR = XF32 ? CW / 3 : CW;       // real X columns per workgroup
   constexpr int NCH = XF32 ? NR / 4 : CW / 8;  // 16-byte chunks per X row in global memory
@@ -71,11 +99,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   constexpr int NIBMAX = NIBT ? NIBT : 4;
   constexpr int TS = ROWS + 4;                 // stride (floats) between columns of a reduction tile
   constexpr int TILE = CW * TS;                // a tile is stored column-major: [column][row]
-  // The epilogue gives every wave its own reduction tile when NW tiles fit in LDS next to the
-  // tables (one round); otherwise the tiles live in the X buffers and are reused over rounds.
-  constexpr bool ONE_ROUND = NW * TILE * 4 <= 148 * 1024;
-  constexpr int FIT = ONE_ROUND ? NW : (NW * XBUF) / (TILE * 4);
-  constexpr int NREG = FIT >= 8 ? (NW < 8 ? NW : 8) : (FIT >= 4 ? 4 : (FIT >= 2 ? 2 : 1));
+  // The epilogue keeps NREG reduction tiles in LDS (over the then idle X buffers): as many as fit
+  // next to the tables, at most one per wave, and a divisor of NW so that the rounds are even.
+  constexpr int FIT = (148 * 1024) / (TILE * 4);
+  constexpr int NREG = largest_divisor_at_most(NW, FIT < 8 ? FIT : 8);
   constexpr int LDSB = (NW * XBUF > NREG * TILE * 4) ? NW * XBUF : NREG * TILE * 4;
   static_assert(!XF32 || NCB % 3 == 0, "fp32 X uses three bf16 terms per column");
   static_assert(FIT >= 1, "a reduction tile must fit in the X buffers");
@@ -112,10 +139,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   // ---- this wave's contiguous slice range [w0, w1) inside the workgroup's [s_begin, s_end)
   const int s_begin = blockIdx.z * slices_per_split;
   const int s_end = min(l_spr, s_begin + slices_per_split);
-  const int per_wave = (s_end - s_begin + NW - 1) / NW;
-  const int w0 = min(s_end, s_begin + wave * per_wave);
-  const int w1 = min(s_end, w0 + per_wave);
-  const int cnt = w1 - w0;
+  const int total = max(0, s_end - s_begin);
+  const int base_cnt = total / NW, extra = total % NW;  // the first `extra` waves take one more
+  const int w0 = s_begin + wave * base_cnt + min(wave, extra);
+  const int cnt = base_cnt + (wave < extra ? 1 : 0);
+  const int w1 = w0 + cnt;
 
   // ---- buffer descriptors
   const int64_t row_bytes = ldx * ESZ;
@@ -138,15 +166,15 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   uint4 xr[NCH];                // X rows of the slice after the one in LDS
   uint4 xr0[PRO2 ? NCH : 1];    // prologue only: X rows of the first slice
   // XDIR layout of a slice buffer: X row r sits at row position pos(r), whose bits 0..5 are bits
-  // 1,4,0,2,3,5 of r, and 16-byte chunk c of that row at chunk c ^ swz(pos), swz = (pos&3)<<1 for
+  // 2,3,0,1,4,5 of r, and 16-byte chunk c of that row at chunk c ^ swz(pos), swz = (pos&3)<<1 for
   // 8-chunk rows and ((pos>>1)&1)<<1 for 4-chunk rows.  The four X rows one transposing read
-  // touches (r, r+2, r+16, r+18) are then four consecutive positions whose 32-byte pieces fall
+  // touches (r, r+4, r+8, r+12) are then four consecutive positions whose 32-byte pieces fall
   // into four different groups of eight banks.  A direct load writes lane l's 16 bytes at
   // (instruction base) + 16 l, so lane l fetches the chunk that belongs there.
   constexpr int LB = (RPI == 8) ? 3 : 4;  // position bits supplied by the lane (XDIR)
   auto row_of_pos = [](int pos) {
-    return ((pos & 1) << 1) | (((pos >> 1) & 1) << 4) | ((pos >> 2) & 1) | (((pos >> 3) & 1) << 2) |
-           (((pos >> 4) & 1) << 3) | (((pos >> 5) & 1) << 5);
+    return ((pos & 1) << 2) | (((pos >> 1) & 1) << 3) | ((pos >> 2) & 1) | (((pos >> 3) & 1) << 1) |
+           (((pos >> 4) & 1) << 4) | (((pos >> 5) & 1) << 5);
   };
   auto swz_of_pos = [](int pos) { return (NCH == 8) ? ((pos & 3) << 1) : (((pos >> 1) & 1) << 1); };
   const int xrow = XDIR ? row_of_pos(lane / NCH) : (XFAST ? lane / NCH : lane);
@@ -162,8 +190,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     const uint32_t sbase = (uint32_t)(s * 64 * row_bytes);  // uniform
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      const uint32_t so = sbase + (uint32_t)(row_of_pos(i << LB) * row_bytes);
-      const uint32_t dst = xbuf_lds + (uint32_t)(which * XSL + i * 1024);
+      const uint32_t so = __builtin_amdgcn_readfirstlane(sbase + (uint32_t)(row_of_pos(i << LB) * row_bytes));
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(xbuf_lds + (uint32_t)(which * XSL + i * 1024));
       asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(x_lane_off),
                    "s"(xdesc), "s"(so)
                    : "memory");
@@ -266,65 +294,71 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     }
   };
 
-  // XDIR: the same loads written as assembly, unconditional (a row block beyond the matrix reads
-  // a zero mask through the descriptor's range check, which makes its operand +-0 whatever the
-  // encrypted bits are).  With every load of the loop hidden from the compiler, the loop's only
-  // waits on memory are the explicit ones below.
+  // XDIR: the compressed words take the same road as X, global memory -> LDS without a register in
+  // between, one dword per lane and stream, unconditionally (a row block beyond the matrix reads a
+  // zero mask through the descriptor's range check, which makes its operand +-0 whatever the
+  // encrypted bits are).  No load of the loop returns into a register, so the compiler has nothing
+  // to wait for and the loop's only waits on memory are the explicit ones below; the words are
+  // picked up from LDS with ordinary reads after such a wait.
   const u32x4 mdesc = {(uint32_t)reinterpret_cast<uint64_t>(l_mask32),
                        (uint32_t)(reinterpret_cast<uint64_t>(l_mask32) >> 32) & 0xffffu, (uint32_t)(l_n_slots * 8),
                        kRsrcFlags};
   const u32x4 edesc = {(uint32_t)reinterpret_cast<uint64_t>(l_enc),
                        (uint32_t)(reinterpret_cast<uint64_t>(l_enc) >> 32) & 0xffffu,
                        (uint32_t)(l_n_slots * l_q * nib), kRsrcFlags};
-  auto load_comp_hidden = [&](int s, Comp &c) {
+  constexpr int NGRP = NCH + KC;  // loads per slice
+  uint32_t *const cbuf = reinterpret_cast<uint32_t *>(xbuf + (XDIR ? PD * XSL : 0));  // after the X slices
+  const uint32_t cbuf_lds = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(size_t)(__attribute__((address_space(3))) uint32_t *)(cbuf));
+  auto dma_dword = [&](uint32_t lds_addr, uint32_t lane_off, const u32x4 &desc, uint32_t so) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds" ::"s"(
+                     __builtin_amdgcn_readfirstlane(lds_addr)),
+                 "v"(lane_off), "s"(desc), "s"(__builtin_amdgcn_readfirstlane(so))
+                 : "memory");
+  };
+  auto load_comp_hidden = [&](int s, int which) {
+    int k = which * KC;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const uint32_t u = (uint32_t)((blockIdx.x * RB + rb) * l_spr + s);  // uniform
-      asm volatile("buffer_load_dword %0, %1, %2, %3 offen"
-                   : "=&v"(c.mw[rb])
-                   : "v"(m_lane_off), "s"(mdesc), "s"(u * 256u)
-                   : "memory");
+      dma_dword(cbuf_lds + (k++) * 256, m_lane_off, mdesc, u * 256u);
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
         const uint32_t so = ((uint32_t)p * (uint32_t)l_n_slots + u * 32u) * (uint32_t)nib;
-        asm volatile("buffer_load_dword %0, %1, %2, %3 offen"
-                     : "=&v"(c.e0[rb][p])
-                     : "v"(e_lane_off), "s"(edesc), "s"(so)
-                     : "memory");
-        if (two_dw)
-          asm volatile("buffer_load_dword %0, %1, %2, %3 offen offset:4"
-                       : "=&v"(c.e1[rb][p])
-                       : "v"(e_lane_off), "s"(edesc), "s"(so)
-                       : "memory");
-        else
-          c.e1[rb][p] = 0u;
+        dma_dword(cbuf_lds + (k++) * 256, e_lane_off, edesc, so);
+        if (two_dw) dma_dword(cbuf_lds + (k++) * 256, e_lane_off, edesc, so + 4u);
       }
     }
   };
-  // every outstanding load of this wave has returned; the registers the hidden loads filled may be
-  // read from here on
-  auto wait_loads = [&](Comp &c) {
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  auto read_comp = [&](int which, Comp &c) {
+    int k = which * KC;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      asm volatile("" : "+v"(c.mw[rb]));
+      c.mw[rb] = cbuf[(k++) * 64 + lane];
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
-        asm volatile("" : "+v"(c.e0[rb][p]));
-        asm volatile("" : "+v"(c.e1[rb][p]));
+        c.e0[rb][p] = cbuf[(k++) * 64 + lane];
+        c.e1[rb][p] = two_dw ? cbuf[(k++) * 64 + lane] : 0u;
       }
     }
+  };
+  // loads return in order: all of them, or all but the newest slice's, have landed
+  auto wait_loads = [&](bool newer_group_in_flight) {
+    if (newer_group_in_flight)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NGRP) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
   // ---- first loads go out before anything else so that they overlap the table build
   Comp ring[2];
   if constexpr (XDIR) {
     if (cnt > 0) {
-      load_comp_hidden(w0, ring[0]);
+      load_comp_hidden(w0, 0);
       dma_x(w0, 0);
     }
-    if (cnt > 1) {
-      load_comp_hidden(w0 + 1, ring[1]);
+    if (PD == 2 && cnt > 1) {
+      load_comp_hidden(w0 + 1, 1);
       dma_x(w0 + 1, 1);
     }
   } else {
@@ -424,11 +458,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   // per-lane address of the transposing reads inside the wave's buffer (see lds_read_tr16)
   const int jj = (lane >> 2) & 3, c4 = lane & 3;
   const uint8_t *tr_ptr =
-      xbuf + (32 * g + 2 * (jj >> 1) + 16 * (jj & 1)) * RSB + (16 * ((lane >> 4) & 1) + 4 * c4) * 2;
+      xbuf + (32 * g + 8 * (jj >> 1) + 4 * (jj & 1)) * RSB + (16 * ((lane >> 4) & 1) + 4 * c4) * 2;
   // XDIR: byte offset of this lane's 8 bytes inside a slice buffer, per column block
   uint32_t tr_off[NCB];
   {
-    const int pos_lane = (jj >> 1) | ((jj & 1) << 1) | (g << 5);
+    const int pos_lane = jj | (g << 5);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       const int c = 4 * cb + 2 * ((lane >> 4) & 1) + (c4 >> 1);
@@ -474,19 +508,19 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   };
   // B operands of MFMA step t of the slice currently in LDS
   auto read_bfrag = [&](int t, bf16x8(&bf)[NCB], int which) {
-    const int par = t >> 1, h = t & 1;
+    const int par = t >> 1, e = t & 1;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       s16x4 lo, hi;
       if constexpr (XDIR) {
-        // X rows +par, +8h, +4 are row positions +4, +16, +8
-        const uint8_t *src = xbuf + which * XSL + tr_off[cb] + (4 * par + 16 * h) * RSB;
+        // X rows +par, +2e, +16 are row positions +4, +8, +16
+        const uint8_t *src = xbuf + which * XSL + tr_off[cb] + (4 * par + 8 * e) * RSB;
         lo = lds_read_tr16(src);
-        hi = lds_read_tr16(src + 8 * RSB);
+        hi = lds_read_tr16(src + 16 * RSB);
       } else {
-        const uint8_t *src = tr_ptr + (8 * h + par) * RSB + cb * 64;
-        lo = lds_read_tr16(src);            // operand slots 0..3
-        hi = lds_read_tr16(src + 4 * RSB);  // operand slots 4..7: four X rows further
+        const uint8_t *src = tr_ptr + (2 * e + par) * RSB + cb * 64;
+        lo = lds_read_tr16(src);             // operand slots 0..3
+        hi = lds_read_tr16(src + 16 * RSB);  // operand slots 4..7: sixteen X rows further
       }
       bf[cb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
@@ -507,8 +541,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     uint32_t Snext[RB][Q];
     if constexpr (XDIR) {
       // both prologue slices have landed in LDS, their compressed words in registers
-      wait_loads(ring[0]);
-      if (cnt > 1) wait_loads(ring[1]);
+      wait_loads(false);
+      read_comp(0, ring[0]);
       // the compiler places its own wait for the patch words here, not at their first use in the loop
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
@@ -526,6 +560,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
     for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t], 0);
     lookup(ring[0], Snext);
+    if constexpr (XDIR && PD == 1) {
+      if (cnt > 1) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the buffers have been read out
+        dma_x(w0 + 1, 0);
+        load_comp_hidden(w0 + 1, 0);
+      }
+    }
 
     for (int sb = w0; sb < w1; sb += 2) {
 #pragma unroll
@@ -543,7 +584,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) mw[rb] = ring[d].mw[rb];
         // patch flips, then interleave sign and mask bits
-        uint32_t Iw[RB][Q][2];
+        uint32_t Iw[RB][Q][4];  // FP4 code words, one per MFMA step
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -568,57 +609,95 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
                 }
               }
             }
-            Iw[rb][p][0] = (mw[rb] & 0x55555555u) | ((S << 1) & 0xAAAAAAAAu);
-            Iw[rb][p][1] = ((mw[rb] >> 1) & 0x55555555u) | (S & 0xAAAAAAAAu);
+            const uint32_t I0 = (mw[rb] & 0x55555555u) | ((S << 1) & 0xAAAAAAAAu);
+            const uint32_t I1 = ((mw[rb] >> 1) & 0x55555555u) | (S & 0xAAAAAAAAu);
+            // (mask, sign) pair k of I_par moves to the top two bits of code k/2 of word k%2
+            Iw[rb][p][0] = (I0 << 2) & 0xCCCCCCCCu;
+            Iw[rb][p][1] = I0 & 0xCCCCCCCCu;
+            Iw[rb][p][2] = (I1 << 2) & 0xCCCCCCCCu;
+            Iw[rb][p][3] = I1 & 0xCCCCCCCCu;
           }
         auto mfma_step = [&](int t) {
-          const int par = t >> 1, h = t & 1;
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int p = 0; p < Q; ++p) {
-              const uint32_t I = Iw[rb][p][par];
-              u32x4 a;
-#pragma unroll
-              for (int dd = 0; dd < 4; ++dd) a[dd] = (I << (14 - 2 * (4 * h + dd))) & 0xC000C000u;
-              const bf16x8 afrag = __builtin_bit_cast(bf16x8, a);
+              const bf16x8 afrag = __builtin_bit_cast(bf16x8, expand_fp4_codes(Iw[rb][p][t]));
 #pragma unroll
               for (int cb = 0; cb < NCB; ++cb)
                 acc[p][rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[t][cb], acc[p][rb][cb], 0, 0, 0);
             }
         };
         mfma_step(0);
-        mfma_step(1);
-        // all operands of slice s are in registers: the LDS buffer takes slice s+1, whose operand
-        // reads follow in program order (LDS ops of one wave execute in order)
-        if constexpr (XDIR) {
-          // slice s+1 was requested one iteration ago: wait for it.  Slice buffer d (slice s) has no
-          // reader left -- its last operand read fed the look-up wait at the top of this iteration --
-          // so slice s+2 may start to land in it.
+        if constexpr (XDIR && PD == 1) {
+          // one buffer: slice s is entirely in operand registers, slice s+1 is landing; it is read
+          // out at the end of the iteration and the buffer handed to slice s+2
+          mfma_step(1);
+          mfma_step(2);
+          mfma_step(3);
+          if (has_next) {
+            __builtin_amdgcn_sched_barrier(0);
+            wait_loads(false);
+            __builtin_amdgcn_sched_barrier(0);
+            read_comp(0, ring[d ^ 1]);
+            lookup(ring[d ^ 1], Snext);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t], 0);
+            if (s + 2 < w1) {
+              __builtin_amdgcn_sched_barrier(0);
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+              dma_x(s + 2, 0);
+              load_comp_hidden(s + 2, 0);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        } else if constexpr (XDIR) {
+          // Slice buffer d (slice s) has no reader left once the operand reads issued during the
+          // previous iteration have returned, so slice s+2 starts to land in it now; its compressed
+          // words replace those of slice s, which the interleave above was the last to use.
+          const bool more = s + 2 < w1;
           __builtin_amdgcn_sched_barrier(0);
-          wait_loads(ring[d ^ 1]);
-          if (s + 2 < w1) {
+          if (more) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             dma_x(s + 2, d);
-            load_comp_hidden(s + 2, ring[d]);
+            load_comp_hidden(s + 2, d);
           }
           __builtin_amdgcn_sched_barrier(0);
+          mfma_step(1);
+          // slice s+1 was requested one iteration ago: wait for it (not for slice s+2)
+          __builtin_amdgcn_sched_barrier(0);
+          wait_loads(more);
+          __builtin_amdgcn_sched_barrier(0);
+          if (has_next) {
+            read_comp(d ^ 1, ring[d ^ 1]);
+            lookup(ring[d ^ 1], Snext);
+            read_bfrag(0, bfrag[0], d ^ 1);
+            read_bfrag(1, bfrag[1], d ^ 1);
+          }
+          mfma_step(2);
+          if (has_next) read_bfrag(2, bfrag[2], d ^ 1);
+          mfma_step(3);
+          if (has_next) read_bfrag(3, bfrag[3], d ^ 1);
         } else {
+          mfma_step(1);
+          // all operands of slice s are in registers: the LDS buffer takes slice s+1, whose operand
+          // reads follow in program order (LDS ops of one wave execute in order)
           if (has_next) store_x(xr);
           if (s + 2 < w1) {
             load_comp(s + 2, ring[d]);
             load_x(s + 2, xr);
           }
-        }
-        if (has_next) {
-          read_bfrag(0, bfrag[0], d ^ 1);
-          read_bfrag(1, bfrag[1], d ^ 1);
-        }
-        mfma_step(2);
-        if (has_next) read_bfrag(2, bfrag[2], d ^ 1);
-        mfma_step(3);
-        if (has_next) {
-          read_bfrag(3, bfrag[3], d ^ 1);
-          lookup(ring[d ^ 1], Snext);
+          if (has_next) {
+            read_bfrag(0, bfrag[0], d ^ 1);
+            read_bfrag(1, bfrag[1], d ^ 1);
+          }
+          mfma_step(2);
+          if (has_next) read_bfrag(2, bfrag[2], d ^ 1);
+          mfma_step(3);
+          if (has_next) {
+            read_bfrag(3, bfrag[3], d ^ 1);
+            lookup(ring[d ^ 1], Snext);
+          }
         }
       }
     }
@@ -770,10 +849,11 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
   }
   const int blocks = (B + 31) / 32;
   if constexpr (Q == 1) {
-    if (blocks == 1) return launch_spmm<1, Q, 2, false, 16>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
     if (x_fast && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
-      return launch_spmm<2, Q, 4, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+      return launch_spmm<2, Q, 4, false, 8, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (x_fast) return launch_spmm<2, Q, 2, false, 12, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
