@@ -127,6 +127,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
                "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_nib), "s"(l_q), "s"(l_n_slots), "s"(Xv), "s"(ldx), "s"(B),
                "s"(Y), "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
+  // a wave that has not sent its first loads yet goes before the waves that already have
+  __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -389,6 +391,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       }
     }
   }
+
+  __builtin_amdgcn_s_setprio(0);
 
   // ---- XOR tables T_b[v] = XOR of the columns 8b..8b+7 of M selected by the bits of v, and alpha
   if constexpr (PRIV_LUT) {
@@ -711,6 +715,9 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   // CW x TS floats (column-major) live in LDS over the (now idle) X buffers; wave w adds into tile w % NREG in round
   // w / NREG, then every thread sums the NREG tiles of its outputs in ascending tile order.
   // acc element i of a lane is row 8*(i/4) + 4*g + i%4, column rl of its 32x32 block.
+  // every wave has left its loop: the X buffers are idle and alpha_s (written by the first waves
+  // without a barrier of its own) is complete
+  __syncthreads();
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -729,7 +736,6 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
           acc[0][rb][cb][4 * j4 + k] = v;  // plane 0's accumulator now holds the scaled sum
         }
     }
-  __syncthreads();
   float *red = reinterpret_cast<float *>(xbuf_all);
   for (int round = 0; round < NW / NREG; ++round) {
     if (wave / NREG == round) {
