@@ -803,7 +803,9 @@ inline void launch_variant(const DevLayer &D, const void *X, int64_t ldx, int B,
                      Y, ldy, sps, atomic);
 }
 
-template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2>
+// XMODE: 0 = the call site may see either layout, 1 = aligned X only, 2 = generic X only (keeps
+// variants that are never launched from being compiled)
+template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2, int XMODE = 0>
 int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, int x_fast,
                     hipStream_t st) {
   constexpr int NR = XF32 ? (32 * NCB) / 3 : 32 * NCB;
@@ -827,10 +829,12 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
   const dim3 grid(row_groups, col_groups, ks);
   const int atomic = ks > 1 ? 1 : 0;
   if (!x_fast) {
-    if constexpr (RB <= 2)  // the larger tiles exist only for the aligned layout
+    if constexpr (XMODE != 1)
       launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
     else
       return XORENC_EUNSUPPORTED;
+  } else if constexpr (XMODE == 2) {
+    return XORENC_EUNSUPPORTED;
   } else {
     switch (D.nib) {
       case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
@@ -855,12 +859,15 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
   }
   const int blocks = (B + 31) / 32;
   if constexpr (Q == 1) {
-    if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (!x_fast) {
+      if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
+      return launch_spmm<2, Q, 2, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
+    }
+    if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
-    if (x_fast && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
-      return launch_spmm<2, Q, 4, false, 8, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
-    if (x_fast) return launch_spmm<2, Q, 2, false, 12, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
-    return launch_spmm<2, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if ((int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
+      return launch_spmm<2, Q, 4, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    return launch_spmm<2, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);

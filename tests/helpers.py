@@ -1,4 +1,5 @@
 """Glue used by the tests: oracle results <-> the arrays the library's binding takes."""
+import dataclasses
 import functools
 
 import numpy as np
@@ -25,9 +26,11 @@ def pack_encoded(enc: "oenc.Encoded"):
 
 
 @functools.lru_cache(maxsize=8)
-def encoded_workload(name: str, m=None, n=None):
-    """(workload, oracle-encoded) for a config, cached for the test session."""
-    wl = make_workload(CONFIGS[name], m=m, n=n)
+def encoded_workload(name: str, m=None, n=None, S=None):
+    """(workload, oracle-encoded) for a config, cached for the test session.  `S` overrides the
+    pruning rate: a low rate with a small n_in gives many patches per slice."""
+    cfg = CONFIGS[name] if S is None else dataclasses.replace(CONFIGS[name], S=S)
+    wl = make_workload(cfg, m=m, n=n)
     return wl, oenc.encode(wl.keep, wl.planes, wl.alpha, wl.M, wl.n)
 
 

@@ -15,10 +15,10 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 2e-3, "f32": 1e-5}
 
 
-def _run(name, m, n, B, dtype, ldx_pad=0):
+def _run(name, m, n, B, dtype, ldx_pad=0, S=None):
     import torch
     import paper_1905_10138_amd as xe
-    wl, enc = encoded_workload(name, m, n)
+    wl, enc = encoded_workload(name, m, n, S)
     L = pack_encoded(enc).to(torch.device("cuda:0"))
     stored, exact = draw_X(wl.n, B, dtype, wl.cfg.seed_X + 1000 * B)
     if dtype == "bf16":
@@ -70,6 +70,23 @@ def test_spmm_full_size_configs(name, B):
     rows = np.random.default_rng(B).integers(0, got.shape[0], size=64)
     for r in rows:
         assert rel_fro(got[r], want[r]) <= 10 * TOL["bf16"]
+
+
+@pytest.mark.parametrize("B,dtype", [(1, "bf16"), (8, "bf16"), (64, "bf16"), (200, "bf16"), (16, "f32")])
+def test_many_patches_per_unit(B, dtype):
+    """Pruning rate 0.75 with n_in = 8: about 16 care bits per slice against 8 encrypted bits, so most
+    slices carry several patches and a wave's range holds more patch entries than its registers prefetch."""
+    wl, enc = encoded_workload("large_q1", 160, 1024, 0.75)
+    assert enc.n_patch.sum() > 3 * enc.n_patch.size
+    got, want = _run("large_q1", 160, 1024, B, dtype, S=0.75)
+    assert rel_fro(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("B", [8, 64])
+def test_patch_counts_from_none_to_a_dozen_per_unit(B):
+    """Pruning rate 0.93: units without patches next to units with up to a dozen."""
+    got, want = _run("large_q1", 320, 1024, B, "bf16", S=0.93)
+    assert rel_fro(got, want) <= TOL["bf16"]
 
 
 def test_tiny_config_fp32_full():
