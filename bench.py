@@ -152,10 +152,10 @@ def roofline_entry(flops, comp_bytes, total_bytes, sec_per_launch, B):
 # Filled in from the committed profile of this exact command; None = not measured.
 MEASURED_TRAFFIC = {
     # profiles/spmm_large_q1_hbm_traffic.md: bytes read + written per launch
-    "large_q1:B1": {"read_bytes": 10.10e6, "write_bytes": 0.07e6},
+    "large_q1:B1": {"read_bytes": 10.11e6, "write_bytes": 0.07e6},
     "large_q1:B8": {"read_bytes": 10.44e6, "write_bytes": 0.52e6},
     "large_q1:B64": {"read_bytes": 14.13e6, "write_bytes": 4.19e6},
-    "large_q1:B256": {"read_bytes": 28.71e6, "write_bytes": 16.78e6},
+    "large_q1:B256": {"read_bytes": 31.16e6, "write_bytes": 16.78e6},
 }
 
 
@@ -254,6 +254,7 @@ def main():
                "tflops": flops * steps / wall / 1e12, "compressed_gbs": runner.comp_bytes * steps / wall / 1e9,
                "replicas": runner.R, "step_bytes": runner.step_bytes, "compressed_bytes": runner.comp_bytes,
                "roofline": roofline_entry(flops, runner.comp_bytes, runner.step_bytes, ev / steps, B)}
+        res["roofline"]["traffic"] = MEASURED_TRAFFIC.get(f"{cfg.name}:B{B}")
         return res, runner, xexact
 
     main_res, runner, xexact = measure(args.batch, args.steps, args.warmup)
@@ -296,9 +297,6 @@ def main():
         "roofline": main_res["roofline"],
         "sweep": sweep,
     }
-    key = f"{cfg.name}:B{args.batch}"
-    if key in MEASURED_TRAFFIC:
-        out["roofline"]["traffic"] = MEASURED_TRAFFIC[key]
     if not args.no_fig1 and cfg.name != "fig1":
         extra["fig1"] = fig1_extra(xe, torch, dev, args)
     if args.copy_calibration:
