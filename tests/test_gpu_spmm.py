@@ -44,7 +44,8 @@ SMALL_CASES = [
     ("fc6", 97, 640, 1, "bf16"), ("fc6", 97, 640, 64, "bf16"), ("fc6", 97, 640, 100, "bf16"), ("fc6", 97, 640, 4, "f32"),
     ("lstm", 130, 3000, 1, "bf16"), ("lstm", 130, 3000, 32, "bf16"), ("lstm", 130, 3000, 40, "f32"),
     ("large_q1", 320, 1024, 1, "bf16"), ("large_q1", 320, 1024, 8, "bf16"), ("large_q1", 320, 1024, 64, "bf16"),
-    ("large_q1", 320, 1024, 256, "bf16"), ("large_q1", 320, 1024, 130, "bf16"),
+    ("large_q1", 320, 1024, 256, "bf16"), ("large_q1", 320, 1024, 130, "bf16"), ("large_q1", 320, 1024, 7, "bf16"),
+    ("lstm", 130, 3000, 3, "bf16"), ("fc6", 97, 640, 8, "bf16"),
     ("large_q2", 96, 4096, 8, "bf16"), ("large_q2", 96, 4096, 256, "bf16"), ("large_q2", 96, 4096, 16, "f32"),
 ]
 
@@ -96,6 +97,10 @@ def test_tiny_config_fp32_full():
 
 def test_odd_leading_dimension_and_unaligned_rows():
     got, want = _run("fig1", 200, 448, 64, "bf16", ldx_pad=3)     # ldx = 67: the 16-bit load path
+    assert rel_fro(got, want) <= TOL["bf16"]
+    got, want = _run("fig1", 200, 448, 8, "bf16", ldx_pad=3)      # few columns, rows not 16-byte aligned
+    assert rel_fro(got, want) <= TOL["bf16"]
+    got, want = _run("fig1", 200, 448, 2, "bf16", ldx_pad=1)
     assert rel_fro(got, want) <= TOL["bf16"]
     got, want = _run("fig1", 200, 448, 6, "f32", ldx_pad=1)
     assert rel_fro(got, want) <= TOL["f32"]
