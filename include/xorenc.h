@@ -36,12 +36,12 @@ extern "C" {
 #define XORENC_API
 #endif
 
-#define XORENC_VERSION 0x00010000u
+#define XORENC_VERSION 0x00020000u
 
 enum {
   XORENC_OK = 0,
   XORENC_EINVAL = -1,       /* null pointer, negative or inconsistent size */
-  XORENC_EUNSUPPORTED = -2, /* n_out != 64, n_in not in {8,16,24,32}, q not in 1..4, unknown dtype */
+  XORENC_EUNSUPPORTED = -2, /* n_out not in {64,128,192,256}, n_in not in {8,16,24,32}, q not in 1..4, unknown dtype */
   XORENC_EALIGN = -3,       /* a device pointer or leading dimension breaks the stated alignment */
   XORENC_EHIP = -4,         /* a HIP runtime call failed; see xorenc_last_hip_error() */
   XORENC_EFORMAT = -5       /* xorenc_pack / xorenc_check_packed found malformed content */
@@ -50,40 +50,46 @@ enum {
 enum { XORENC_OUT_PLANES = 0, XORENC_OUT_F32 = 1, XORENC_OUT_BF16 = 2 };
 enum { XORENC_X_F32 = 0, XORENC_X_BF16 = 1 };
 
-/* Rows are grouped in blocks of XORENC_ROWS_PER_UNIT; a "unit" is one 64-column slice
- * position of one row block (32 slices, one per row). */
+/* Rows are grouped in blocks of XORENC_ROWS_PER_UNIT; a "unit" is one 64-column word
+ * position of one row block (32 words, one per row).  A slice of n_out = 64 J bits (J = 1..4) is J
+ * consecutive 64-bit words of a row that share one encrypted vector. */
 #define XORENC_ROWS_PER_UNIT 32
-#define XORENC_N_OUT 64
+#define XORENC_WORD_BITS 64
+#define XORENC_MAX_N_OUT 256
 
 /*
  * One encrypted weight matrix in the packed device layout.
  *
  * Logical matrix W: m rows (outputs) x n columns (inputs).  Columns are padded with pruned
- * columns to n_pad = 64*ceil(n/64) so that a slice never straddles rows (Section 3.1 applied
- * to the padded matrix); spr = n_pad/64 slices per row.  Rows are padded to
- * m_pad = 32*ceil(m/32) with fully pruned rows.  Slot index of (row r, slice s):
- *     slot(r, s) = ((r/32)*spr + s)*32 + (r % 32)            ("unit-major")
- * so the 32 slices a unit holds are contiguous.  n_slots = m_pad*spr, n_units = n_slots/32.
+ * columns to n_pad = n_out*ceil(n/n_out) so that a slice never straddles rows (Section 3.1 applied
+ * to the padded matrix); spr = n_pad/64 words per row, espr = n_pad/n_out slices per row, J = n_out/64.
+ * Rows are padded to m_pad = 32*ceil(m/32) with fully pruned rows.  Word index of (row r, word s) and
+ * slice index of (row r, slice S):
+ *     slot(r, s)  = ((r/32)*spr  + s)*32 + (r % 32)          ("unit-major")
+ *     eslot(r, S) = ((r/32)*espr + S)*32 + (r % 32)
+ * so the 32 words a unit holds are contiguous.  n_slots = m_pad*spr, n_units = n_slots/32,
+ * n_eslots = m_pad*espr.  Word s of a row holds bits 64 (s % J) .. 64 (s % J) + 63 of slice s / J.
  *
  *   mask      DEV  uint64[n_slots], 8-byte aligned.  Bit j of mask[slot(r,s)] = 1 iff weight
  *                  (r, 64 s + j) is kept (care); padding rows/columns are 0.
- *   enc       DEV  uint8[q][n_slots][n_in/8]: the n_in encrypted bits of each slice of each
+ *   enc       DEV  uint8[q][n_eslots][n_in/8]: the n_in encrypted bits of each slice of each
  *                  plane, little endian (bit j of the integer = x_j).  4-byte aligned.
  *   patch_off DEV  uint32[q*n_units + 1], 4-byte aligned, non-decreasing;
  *                  entries [patch_off[p*n_units+u], patch_off[p*n_units+u+1]) belong to unit u
  *                  of plane p.
  *   patch     DEV  uint16[patch_off[q*n_units]], 2-byte aligned; entry = (r%32)<<6 | bit: flip
- *                  bit `bit` (0..63) of the decrypted slice of row r%32 of that unit.  This is the
+ *                  bit `bit` (0..63) of the decrypted word of row r%32 of that unit.  This is the
  *                  paper's (n_patch, d_patch) re-arranged for random access: n_patch of a slice =
- *                  number of its entries, d_patch = their bit fields.  May be NULL if there are none.
+ *                  number of entries of its J words, d_patch = 64 (word % J) + bit.  May be NULL if
+ *                  there are none.
  *   alpha     DEV  float[q][m], 4-byte aligned: per-row scale of each plane.
- *   M_rows    HOST uint32[64]: bit j of M_rows[i] = M[i][j], the XOR-gate network (Section 3.1);
+ *   M_rows    HOST uint32[n_out]: bit j of M_rows[i] = M[i][j], the XOR-gate network (Section 3.1);
  *                  bits >= n_in must be 0.
  */
 typedef struct xorenc_layer {
   uint32_t struct_size; /* = sizeof(xorenc_layer), ABI guard */
   int32_t m, n;
-  int32_t n_out; /* 64 */
+  int32_t n_out; /* 64, 128, 192 or 256 */
   int32_t n_in;  /* 8, 16, 24 or 32 */
   int32_t q;     /* 1..4 bit-planes */
   const uint32_t *M_rows;
@@ -97,9 +103,10 @@ typedef struct xorenc_layer {
 /* Element counts of the packed buffers for a shape (HOST arithmetic only). */
 typedef struct xorenc_sizes {
   int64_t n_pad, m_pad, spr, n_slots, n_units;
-  int64_t enc_bytes;       /* q*n_slots*n_in/8 */
+  int64_t enc_bytes;       /* q*n_eslots*n_in/8 */
   int64_t mask_words;      /* n_slots */
   int64_t patch_off_words; /* q*n_units + 1 */
+  int64_t espr, n_eslots;  /* slices per row, m_pad*espr */
 } xorenc_sizes;
 
 XORENC_API uint32_t xorenc_version(void);
@@ -107,28 +114,30 @@ XORENC_API const char *xorenc_strerror(int32_t code);
 /* hipError_t value of the last failed HIP call made by this library on the calling thread. */
 XORENC_API int32_t xorenc_last_hip_error(void);
 
-XORENC_API int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, xorenc_sizes *out /*HOST*/);
+XORENC_API int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                    xorenc_sizes *out /*HOST*/);
 
 /*
  * Re-arrange the paper's compressed format (Section 3.2: w^c_1..l, n_patch, d_patch per plane,
- * slices in row-major order of the column-padded matrix, l = m*spr) into the packed layout.
+ * slices in row-major order of the column-padded matrix, l = m*espr) into the packed layout.
  * All pointers HOST.  Pure data movement, no arithmetic of the method.
- *   w_c      uint32[q][l]   encrypted bits of slice t = r*spr + s (bit j = x_j)
- *   keep     uint64[l]      care mask of slice t (bit j = column 64 s + j kept)
+ *   w_c      uint32[q][l]   encrypted bits of slice t = r*espr + S (bit j = x_j)
+ *   keep     uint64[m*spr]  care mask, row-major words: word r*spr + s (bit j = column 64 s + j kept)
  *   n_patch  uint16[q][l]   number of patches of each slice
- *   d_patch  uint8[]        bit positions, plane by plane, slice by slice, ascending within a slice;
- *                           n_d_patch = total length = sum of n_patch
+ *   d_patch  uint8[]        bit positions (0 .. n_out-1), plane by plane, slice by slice, ascending
+ *                           within a slice; n_d_patch = total length = sum of n_patch
  * Outputs sized by xorenc_get_sizes (patch: n_d_patch entries).
- * XORENC_EFORMAT if sum(n_patch) != n_d_patch, a position is >= 64 or not ascending.
+ * XORENC_EFORMAT if sum(n_patch) != n_d_patch, a position is >= n_out or not ascending.
  */
-XORENC_API int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *w_c, const uint64_t *keep,
-                    const uint16_t *n_patch, const uint8_t *d_patch, int64_t n_d_patch, uint8_t *enc_out,
-                    uint64_t *mask_out, uint32_t *patch_off_out, uint16_t *patch_out);
+XORENC_API int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *w_c,
+                               const uint64_t *keep, const uint16_t *n_patch, const uint8_t *d_patch,
+                               int64_t n_d_patch, uint8_t *enc_out, uint64_t *mask_out, uint32_t *patch_off_out,
+                               uint16_t *patch_out);
 
 /* Inverse of xorenc_pack (all pointers HOST; d_patch_out holds patch_off[q*n_units] bytes). */
-XORENC_API int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint8_t *enc, const uint64_t *mask,
-                      const uint32_t *patch_off, const uint16_t *patch, uint32_t *w_c_out, uint64_t *keep_out,
-                      uint16_t *n_patch_out, uint8_t *d_patch_out);
+XORENC_API int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint8_t *enc,
+                                 const uint64_t *mask, const uint32_t *patch_off, const uint16_t *patch,
+                                 uint32_t *w_c_out, uint64_t *keep_out, uint16_t *n_patch_out, uint8_t *d_patch_out);
 
 /*
  * Content check of a packed layer whose buffers are all HOST copies: offsets non-decreasing,
@@ -139,20 +148,21 @@ XORENC_API int32_t xorenc_check_packed(const xorenc_layer *layer_with_host_buffe
 
 /*
  * Re-arrange a dense 0/1 byte matrix (HOST, row-major m x n, leading dimension ld >= n bytes) into
- * unit-major 64-bit slice words (HOST uint64[n_slots]): bit j of word slot(r,s) = a[r][64 s + j] != 0;
- * padding rows and columns are 0.  Used to hand masks and quantised bit-planes to xorenc_encode.
+ * unit-major 64-bit words (HOST uint64[n_slots] for this n_out): bit j of word slot(r,s) =
+ * a[r][64 s + j] != 0; padding rows and columns are 0.  Used to hand masks and quantised bit-planes
+ * to xorenc_encode.
  */
-XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, const uint8_t *a, int64_t ld, uint64_t *out);
+XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, int32_t n_out, const uint8_t *a, int64_t ld, uint64_t *out);
 
 /*
  * Encoder on the GPU: Algorithm 1 (patch searching) of Section 3.3 for every slice of every plane,
  * one slice per lane.  Care bits are visited in ascending position; an equation that makes the
  * system unsolvable is dropped and becomes a patch; free variables of the final system are 0, so
  * the result is the unique solution the reduced row-echelon form gives.
- *   M_rows     HOST uint32[64]
+ *   M_rows     HOST uint32[n_out]
  *   mask       DEV  uint64[n_slots]      care mask, unit-major (the layer's mask buffer itself)
  *   planes     DEV  uint64[q][n_slots]   quantised bits, unit-major; bits at pruned positions are ignored
- *   enc_out    DEV  uint8[q][n_slots][n_in/8]
+ *   enc_out    DEV  uint8[q][n_eslots][n_in/8]
  *   patch_off_out DEV uint32[q*n_units + 1]
  *   patch_out  DEV  uint16[patch_capacity]; entries beyond the capacity are not written.  The caller
  *              must compare patch_off_out[q*n_units] (the true total) with patch_capacity after the
@@ -160,7 +170,7 @@ XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, const uint8_t *a, int6
  *   workspace  DEV  uint64[q*n_slots] + uint32[q*n_units] bytes, 8-byte aligned (scratch, contents undefined after)
  * Three kernels are enqueued on hip_stream; nothing synchronises.
  */
-XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *M_rows,
+XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *M_rows,
                                  const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
                                  uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity,
                                  void *workspace, int64_t workspace_bytes, void *hip_stream);
@@ -168,7 +178,7 @@ XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, 
 /*
  * Decode only (Sections 3.1-3.2 + mask + dequantisation).
  *   XORENC_OUT_PLANES: out = DEV uint64[q][m*spr], word p*(m*spr) + r*spr + s = decrypted, patched
- *                      slice with pruned and padding positions forced to 0; ld_out ignored.
+ *                      64-bit word with pruned and padding positions forced to 0; ld_out ignored.
  *   XORENC_OUT_F32:    out = DEV float, row-major m x n, leading dimension ld_out >= n (elements):
  *                      W[r][c] = keep ? ((+-alpha_1) + (+-alpha_2)) + ... in fp32, left to right : +0.0
  *   XORENC_OUT_BF16:   out = DEV bf16 (uint16 patterns): round-to-nearest-even of the fp32 value.

@@ -38,7 +38,8 @@ class _Layer(ctypes.Structure):
 
 class _Sizes(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int64) for k in
-                ("n_pad", "m_pad", "spr", "n_slots", "n_units", "enc_bytes", "mask_words", "patch_off_words")]
+                ("n_pad", "m_pad", "spr", "n_slots", "n_units", "enc_bytes", "mask_words", "patch_off_words",
+                 "espr", "n_eslots")]
 
 
 def library_path() -> str:
@@ -63,17 +64,17 @@ def load_library():
     lib.xorenc_last_hip_error.restype = i32
     lib.xorenc_last_hip_error.argtypes = []
     lib.xorenc_get_sizes.restype = i32
-    lib.xorenc_get_sizes.argtypes = [i32, i32, i32, i32, ctypes.POINTER(_Sizes)]
+    lib.xorenc_get_sizes.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(_Sizes)]
     lib.xorenc_pack.restype = i32
-    lib.xorenc_pack.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.xorenc_pack.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.xorenc_unpack.restype = i32
-    lib.xorenc_unpack.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.xorenc_unpack.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.xorenc_check_packed.restype = i32
     lib.xorenc_check_packed.argtypes = [ctypes.POINTER(_Layer)]
     lib.xorenc_pack_bits.restype = i32
-    lib.xorenc_pack_bits.argtypes = [i32, i32, vp, i64, vp]
+    lib.xorenc_pack_bits.argtypes = [i32, i32, i32, vp, i64, vp]
     lib.xorenc_encode.restype = i32
-    lib.xorenc_encode.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    lib.xorenc_encode.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
     lib.xorenc_decode.restype = i32
     lib.xorenc_decode.argtypes = [ctypes.POINTER(_Layer), i32, vp, i64, vp]
     lib.xorenc_spmm.restype = i32
@@ -95,9 +96,9 @@ def _check(code: int, where: str):
         raise XorencError(int(code), where)
 
 
-def get_sizes(m: int, n: int, n_in: int, q: int) -> dict:
+def get_sizes(m: int, n: int, n_in: int, q: int, n_out: int = 64) -> dict:
     s = _Sizes()
-    _check(load_library().xorenc_get_sizes(m, n, n_in, q, ctypes.byref(s)), "xorenc_get_sizes")
+    _check(load_library().xorenc_get_sizes(m, n, n_in, q, n_out, ctypes.byref(s)), "xorenc_get_sizes")
     return {k: int(getattr(s, k)) for k, _ in _Sizes._fields_}
 
 
@@ -122,6 +123,7 @@ class PackedLayer:
     patch_off: object
     patch: object
     alpha: object
+    n_out: int = 64               # bits per slice: 64, 128, 192 or 256
 
     @property
     def on_device(self) -> bool:
@@ -135,7 +137,7 @@ class PackedLayer:
         return buf.data_ptr() if buf.numel() else None
 
     def c_struct(self) -> _Layer:
-        return _Layer(ctypes.sizeof(_Layer), self.m, self.n, 64, self.n_in, self.q,
+        return _Layer(ctypes.sizeof(_Layer), self.m, self.n, self.n_out, self.n_in, self.q,
                       self.M_rows.ctypes.data, self._ptr(self.enc), self._ptr(self.mask),
                       self._ptr(self.patch_off), self._ptr(self.patch), self._ptr(self.alpha))
 
@@ -147,14 +149,14 @@ class PackedLayer:
         # torch has no uint64/uint32/uint16 arithmetic needs here: move raw bytes with signed views
         return PackedLayer(self.m, self.n, self.n_in, self.q, self.M_rows,
                            mv(self.enc), mv(self.mask, np.int64), mv(self.patch_off, np.int32),
-                           mv(self.patch, np.int16), mv(self.alpha))
+                           mv(self.patch, np.int16), mv(self.alpha), self.n_out)
 
     def to_host(self) -> "PackedLayer":
         def mv(t, dt):
             return t.detach().cpu().contiguous().numpy().view(dt)
         return PackedLayer(self.m, self.n, self.n_in, self.q, self.M_rows, mv(self.enc, np.uint8),
                            mv(self.mask, np.uint64), mv(self.patch_off, np.uint32), mv(self.patch, np.uint16),
-                           mv(self.alpha, np.float32))
+                           mv(self.alpha, np.float32), self.n_out)
 
     def compressed_bytes(self) -> int:
         """Bytes of every device buffer a kernel reads for this layer."""
@@ -163,65 +165,69 @@ class PackedLayer:
         return sum(nb(b) for b in (self.enc, self.mask, self.patch_off, self.patch, self.alpha))
 
 
-def pack(m, n, n_in, q, w_c, keep, n_patch, d_patch, alpha, M_rows) -> PackedLayer:
-    """xorenc_pack: paper format (host NumPy arrays) -> packed layout (host NumPy arrays)."""
+def pack(m, n, n_in, q, w_c, keep, n_patch, d_patch, alpha, M_rows, n_out: int = 64) -> PackedLayer:
+    """xorenc_pack: paper format (host NumPy arrays) -> packed layout (host NumPy arrays).
+    w_c, n_patch: one entry per n_out-bit slice; keep: uint64 words, row-major (m, spr)."""
     lib = load_library()
-    sz = get_sizes(m, n, n_in, q)
-    l = m * sz["spr"]
+    sz = get_sizes(m, n, n_in, q, n_out)
+    l = m * sz["espr"]
     w_c = _as(w_c, np.uint32).reshape(q, l)
-    keep = _as(keep, np.uint64).reshape(l)
+    keep = _as(keep, np.uint64).reshape(m * sz["spr"])
     n_patch = _as(n_patch, np.uint16).reshape(q, l)
     d_patch = _as(d_patch, np.uint8).reshape(-1)
     alpha = _as(alpha, np.float32).reshape(q, m)
-    M_rows = _as(M_rows, np.uint32).reshape(64)
+    M_rows = _as(M_rows, np.uint32).reshape(n_out)
     enc = np.empty(sz["enc_bytes"], np.uint8)
     mask = np.empty(sz["mask_words"], np.uint64)
     patch_off = np.empty(sz["patch_off_words"], np.uint32)
     patch = np.empty(d_patch.size, np.uint16)
-    _check(lib.xorenc_pack(m, n, n_in, q, _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
+    _check(lib.xorenc_pack(m, n, n_in, q, n_out, _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
                            _np_ptr(d_patch) if d_patch.size else None, d_patch.size, _np_ptr(enc), _np_ptr(mask),
                            _np_ptr(patch_off), _np_ptr(patch) if patch.size else None), "xorenc_pack")
-    return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch, alpha)
+    return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch, alpha, n_out)
 
 
 def unpack(layer: PackedLayer):
-    """xorenc_unpack on a host layer: returns (w_c uint32[q,l], keep uint64[l], n_patch uint16[q,l], d_patch uint8[])."""
+    """xorenc_unpack on a host layer: returns (w_c uint32[q,l], keep uint64[m*spr], n_patch uint16[q,l],
+    d_patch uint8[]) with l = m * espr slices per plane."""
     if layer.on_device:
         raise ValueError("unpack needs host buffers")
     lib = load_library()
-    sz = get_sizes(layer.m, layer.n, layer.n_in, layer.q)
-    l = layer.m * sz["spr"]
+    sz = get_sizes(layer.m, layer.n, layer.n_in, layer.q, layer.n_out)
+    l = layer.m * sz["espr"]
     w_c = np.empty((layer.q, l), np.uint32)
-    keep = np.empty(l, np.uint64)
+    keep = np.empty(layer.m * sz["spr"], np.uint64)
     n_patch = np.empty((layer.q, l), np.uint16)
     d_patch = np.empty(int(layer.patch_off[-1]), np.uint8)
-    _check(lib.xorenc_unpack(layer.m, layer.n, layer.n_in, layer.q, _np_ptr(layer.enc), _np_ptr(layer.mask),
-                             _np_ptr(layer.patch_off), _np_ptr(layer.patch) if layer.patch.size else None,
+    _check(lib.xorenc_unpack(layer.m, layer.n, layer.n_in, layer.q, layer.n_out, _np_ptr(layer.enc),
+                             _np_ptr(layer.mask), _np_ptr(layer.patch_off),
+                             _np_ptr(layer.patch) if layer.patch.size else None,
                              _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
                              _np_ptr(d_patch) if d_patch.size else None), "xorenc_unpack")
     return w_c, keep, n_patch, d_patch
 
 
-def pack_bits(a: np.ndarray) -> np.ndarray:
-    """xorenc_pack_bits: dense 0/1 matrix (m, n) -> unit-major uint64 slice words (host)."""
+def pack_bits(a: np.ndarray, n_out: int = 64) -> np.ndarray:
+    """xorenc_pack_bits: dense 0/1 matrix (m, n) -> unit-major uint64 words (host), columns padded to n_out."""
     a = np.ascontiguousarray(a).view(np.uint8) if a.dtype == np.bool_ else _as(a, np.uint8)
     m, n = a.shape
-    spr, nrb = (n + 63) // 64, (m + 31) // 32
+    spr, nrb = -(-n // n_out) * (n_out // 64), (m + 31) // 32
     out = np.empty(nrb * 32 * spr, np.uint64)
-    _check(load_library().xorenc_pack_bits(m, n, _np_ptr(a), a.strides[0], _np_ptr(out)), "xorenc_pack_bits")
+    _check(load_library().xorenc_pack_bits(m, n, n_out, _np_ptr(a), a.strides[0], _np_ptr(out)), "xorenc_pack_bits")
     return out
 
 
-def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[int] = None) -> PackedLayer:
+def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[int] = None,
+           n_out: int = 64) -> PackedLayer:
     """xorenc_encode on the current stream.  mask: int64 GPU tensor [n_slots] (unit-major words),
     planes: int64 GPU tensor [q, n_slots], alpha: float32 GPU tensor [q, m].  Returns a device
     PackedLayer that shares `mask` and `alpha`.  Synchronises once to read the patch total (the
     C call itself does not) and retries with a larger patch buffer if the first was too small."""
     import torch
     lib = load_library()
-    sz = get_sizes(m, n, n_in, q)
+    sz = get_sizes(m, n, n_in, q, n_out)
     dev = mask.device
-    M_rows = _as(M_rows, np.uint32).reshape(64)
+    M_rows = _as(M_rows, np.uint32).reshape(n_out)
     if mask.numel() != sz["n_slots"] or planes.numel() != q * sz["n_slots"]:
         raise ValueError("mask/planes do not have n_slots words per plane")
     enc = torch.zeros(sz["enc_bytes"], dtype=torch.uint8, device=dev)
@@ -231,7 +237,7 @@ def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[
     cap = int(patch_capacity) if patch_capacity is not None else max(1024, q * sz["n_slots"] // 8)
     while True:
         patch = torch.empty(cap, dtype=torch.int16, device=dev)
-        _check(lib.xorenc_encode(m, n, n_in, q, _np_ptr(M_rows), ctypes.c_void_p(mask.data_ptr()),
+        _check(lib.xorenc_encode(m, n, n_in, q, n_out, _np_ptr(M_rows), ctypes.c_void_p(mask.data_ptr()),
                                  ctypes.c_void_p(planes.data_ptr()), ctypes.c_void_p(enc.data_ptr()),
                                  ctypes.c_void_p(patch_off.data_ptr()), ctypes.c_void_p(patch.data_ptr()), cap,
                                  ctypes.c_void_p(ws.data_ptr()), ws.numel() * 8, _stream_ptr()), "xorenc_encode")
@@ -239,7 +245,7 @@ def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[
         if total <= cap:
             break
         cap = total
-    return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch[:total], alpha)
+    return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch[:total], alpha, n_out)
 
 
 def check_packed(layer: PackedLayer) -> int:
@@ -262,7 +268,7 @@ def decode(layer: PackedLayer, out_kind: int = OUT_PLANES, out=None):
     if not layer.on_device:
         raise ValueError("decode needs a layer whose buffers are on the GPU")
     dev = layer.enc.device
-    spr = (layer.n + 63) // 64
+    spr = -(-layer.n // layer.n_out) * (layer.n_out // 64)
     if out is None:
         if out_kind == OUT_PLANES:
             out = torch.empty((layer.q, layer.m * spr), dtype=torch.int64, device=dev)

@@ -20,9 +20,8 @@ int32_t xorenc_internal_check_launch(void) {
 
 int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   if (!layer || layer->struct_size != sizeof(xorenc_layer)) return XORENC_EINVAL;
-  if (layer->n_out != XORENC_N_OUT) return XORENC_EUNSUPPORTED;
   xorenc_sizes sz;
-  const int32_t rc = xorenc_get_sizes(layer->m, layer->n, layer->n_in, layer->q, &sz);
+  const int32_t rc = xorenc_get_sizes(layer->m, layer->n, layer->n_in, layer->q, layer->n_out, &sz);
   if (rc != XORENC_OK) return rc;
   if (!layer->M_rows || !layer->enc || !layer->mask || !layer->patch_off || !layer->alpha) return XORENC_EINVAL;
   if (sz.n_slots > (int64_t)1 << 31) return XORENC_EUNSUPPORTED;
@@ -38,21 +37,25 @@ int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   D->m = layer->m;
   D->n = layer->n;
   D->spr = (int32_t)sz.spr;
+  D->espr = (int32_t)sz.espr;
+  D->J = layer->n_out / 64;
   D->nrb = (int32_t)(sz.m_pad / 32);
   D->n_units = (int32_t)sz.n_units;
   D->nib = nib;
   D->q = layer->q;
   D->n_slots = sz.n_slots;
-  for (int j = 0; j < XORENC_MAX_N_IN; ++j) D->Mcol_lo[j] = D->Mcol_hi[j] = 0;
-  for (int i = 0; i < 64; ++i) {
+  D->n_eslots = sz.n_eslots;
+  for (int j = 0; j < XORENC_MAX_J * XORENC_MAX_N_IN; ++j) D->Mcol_lo[j] = D->Mcol_hi[j] = 0;
+  for (int i = 0; i < layer->n_out; ++i) {
     const uint32_t row = layer->M_rows[i];
     if (layer->n_in < 32 && (row >> layer->n_in)) return XORENC_EINVAL;
+    const int w = i / 64, ii = i % 64;
     for (int j = 0; j < layer->n_in; ++j)
       if ((row >> j) & 1) {
-        if (i < 32)
-          D->Mcol_lo[j] |= 1u << i;
+        if (ii < 32)
+          D->Mcol_lo[w * XORENC_MAX_N_IN + j] |= 1u << ii;
         else
-          D->Mcol_hi[j] |= 1u << (i - 32);
+          D->Mcol_hi[w * XORENC_MAX_N_IN + j] |= 1u << (ii - 32);
       }
   }
   return XORENC_OK;
@@ -64,7 +67,7 @@ namespace {
 // decode kernel: one slot (row, slice) per lane
 
 __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, void *out, int64_t ld) {
-  __shared__ uint32_t lut[XORENC_MAX_N_IN / 8 * 512];
+  __shared__ uint32_t lut[XORENC_MAX_J * (XORENC_MAX_N_IN / 8) * 512];
   build_xor_tables(lut, L);
   __syncthreads();
 
@@ -85,10 +88,13 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
     w[p] = 0;
     a[p] = 0.f;
     if (p < L.q && valid) {
-      const uint32_t x = load_enc(L.enc + ((int64_t)p * L.n_slots + slot) * L.nib, L.nib);
+      // word s of the row belongs to slice s / J and is word s % J of it
+      const int64_t eslot = ((int64_t)rb * L.espr + s / L.J) * 32 + rr;
+      const int wsel = s % L.J;
+      const uint32_t x = load_enc(L.enc + ((int64_t)p * L.n_eslots + eslot) * L.nib, L.nib);
       uint32_t lo = 0, hi = 0;
       for (int b = 0; b < L.nib; ++b) {
-        const int e = (b << 8) + ((x >> (8 * b)) & 255);
+        const int e = ((wsel * L.nib + b) << 8) + ((x >> (8 * b)) & 255);
         lo ^= lut[2 * e];
         hi ^= lut[2 * e + 1];
       }

@@ -17,22 +17,26 @@ struct DevLayer {
   const uint16_t *patch;
   const float *alpha;
   int32_t m, n, spr, nrb, n_units, nib, q;
-  int64_t n_slots;
-  uint32_t Mcol_lo[XORENC_MAX_N_IN];  // column j of M, rows 0..31
-  uint32_t Mcol_hi[XORENC_MAX_N_IN];  // column j of M, rows 32..63
+  int32_t J, espr;  // 64-bit words per slice (n_out/64), slices per row
+  int64_t n_slots, n_eslots;
+  // column j of M restricted to word w of a slice (rows 64 w .. 64 w + 63): lower and upper 32 rows
+  uint32_t Mcol_lo[XORENC_MAX_J * XORENC_MAX_N_IN];
+  uint32_t Mcol_hi[XORENC_MAX_J * XORENC_MAX_N_IN];
 };
 
 
-// T_b[v] for b < nib, v < 256; entry (b*256+v) holds {low 32 rows, high 32 rows}.
+// T_{w,b}[v] for word w < J of a slice, b < nib, v < 256; entry ((w*nib + b)*256 + v) holds
+// {low 32 rows, high 32 rows} of the XOR of the columns 8b..8b+7 of M selected by the bits of v.
 static __device__ inline void build_xor_tables(uint32_t *lut, const DevLayer &L) {
-  for (int idx = threadIdx.x; idx < L.nib * 256; idx += blockDim.x) {
-    const int b = idx >> 8, v = idx & 255;
+  for (int idx = threadIdx.x; idx < L.J * L.nib * 256; idx += blockDim.x) {
+    const int wb = idx >> 8, v = idx & 255;
+    const int w = wb / L.nib, b = wb % L.nib;
     uint32_t lo = 0, hi = 0;
 #pragma unroll
     for (int t = 0; t < 8; ++t)
       if ((v >> t) & 1) {
-        lo ^= L.Mcol_lo[8 * b + t];
-        hi ^= L.Mcol_hi[8 * b + t];
+        lo ^= L.Mcol_lo[w * XORENC_MAX_N_IN + 8 * b + t];
+        hi ^= L.Mcol_hi[w * XORENC_MAX_N_IN + 8 * b + t];
       }
     lut[2 * idx] = lo;
     lut[2 * idx + 1] = hi;

@@ -22,46 +22,59 @@ struct EncParams {
   uint8_t *enc;
   uint64_t *pbits;      // [q][n_slots] patch bitmaps (workspace)
   uint32_t *counts;     // [q*n_units] patches per unit (workspace)
-  int64_t n_slots;
-  int32_t n_units, n_in, nib, q;
-  uint32_t M_rows[64];
+  int64_t n_slots, n_eslots;
+  int32_t n_units, n_in, nib, q, J, spr, espr;
+  uint32_t M_rows[XORENC_MAX_N_OUT];
 };
 
 __global__ __launch_bounds__(ENC_THREADS) void encode_slices_kernel(EncParams P) {
   __shared__ uint32_t basis[XORENC_MAX_N_IN][ENC_THREADS];
   const int tid = threadIdx.x;
-  const int64_t gid = (int64_t)blockIdx.x * ENC_THREADS + tid;  // (plane, slot) flattened
-  const int64_t total = (int64_t)P.q * P.n_slots;
+  const int64_t gid = (int64_t)blockIdx.x * ENC_THREADS + tid;  // (plane, slice) flattened, slices in eslot order
+  const int64_t total = (int64_t)P.q * P.n_eslots;
   const bool valid = gid < total;
-  const int64_t slot = valid ? gid % P.n_slots : 0;
-  const int p = valid ? (int)(gid / P.n_slots) : 0;
+  const int64_t eslot = valid ? gid % P.n_eslots : 0;
+  const int p = valid ? (int)(gid / P.n_eslots) : 0;
+  // eslot = (rb*espr + S)*32 + rr; word w of the slice is slot (rb*spr + S*J + w)*32 + rr
+  const int rr = (int)(eslot & 31);
+  const int64_t eu = eslot >> 5;
+  const int64_t rb = eu / P.espr, S = eu % P.espr;
+  const int64_t unit0 = rb * P.spr + S * P.J;
 
-  uint64_t care = valid ? P.mask[slot] : 0ull;
-  const uint64_t bits = valid ? P.planes[(int64_t)p * P.n_slots + slot] : 0ull;
   uint32_t have = 0;     // bit j: a basis row with pivot j exists
   uint32_t rhsbits = 0;  // bit j: right-hand side of that row
-  uint64_t patches = 0;
-
-  while (care) {
-    const int i = __builtin_ctzll(care);
-    care &= care - 1;
-    uint32_t row = P.M_rows[i];
-    uint32_t rhs = (uint32_t)((bits >> i) & 1);
-    uint32_t t = row & have;
-    while (t) {  // reduce, ascending pivots
-      const int j = __builtin_ctz(t);
-      row ^= basis[j][tid];
-      rhs ^= (rhsbits >> j) & 1u;
-      t = row & have & ~((2u << j) - 1u);
+  for (int w = 0; w < P.J; ++w) {  // uniform; care bits in ascending position over the whole slice
+    const int64_t slot = (unit0 + w) * 32 + rr;
+    uint64_t care = valid ? P.mask[slot] : 0ull;
+    const uint64_t bits = valid ? P.planes[(int64_t)p * P.n_slots + slot] : 0ull;
+    uint64_t patches = 0;
+    while (care) {
+      const int i = __builtin_ctzll(care);
+      care &= care - 1;
+      uint32_t row = P.M_rows[64 * w + i];
+      uint32_t rhs = (uint32_t)((bits >> i) & 1);
+      uint32_t t = row & have;
+      while (t) {  // reduce, ascending pivots
+        const int j = __builtin_ctz(t);
+        row ^= basis[j][tid];
+        rhs ^= (rhsbits >> j) & 1u;
+        t = row & have & ~((2u << j) - 1u);
+      }
+      if (row == 0) {
+        if (rhs) patches |= 1ull << i;  // 0 ... 0 | 1: unsolvable, the equation is dropped
+        continue;
+      }
+      const int piv = __builtin_ctz(row);
+      basis[piv][tid] = row;
+      have |= 1u << piv;
+      rhsbits |= rhs << piv;
     }
-    if (row == 0) {
-      if (rhs) patches |= 1ull << i;  // 0 ... 0 | 1: unsolvable, the equation is dropped
-      continue;
-    }
-    const int piv = __builtin_ctz(row);
-    basis[piv][tid] = row;
-    have |= 1u << piv;
-    rhsbits |= rhs << piv;
+    if (valid) P.pbits[(int64_t)p * P.n_slots + slot] = patches;
+    // patches per unit = sum over the 32 lanes that share it (n_eslots is a multiple of 32)
+    int cnt = __builtin_popcountll(patches);
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_down(cnt, o, 32);
+    if (valid && rr == 0) P.counts[(int64_t)p * P.n_units + unit0 + w] = (uint32_t)cnt;
   }
   // back-substitution, free variables = 0, highest pivot first
   uint32_t x = 0;
@@ -74,15 +87,9 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_slices_kernel(EncParams P)
     x |= v << j;
   }
   if (valid) {
-    uint8_t *dst = P.enc + ((int64_t)p * P.n_slots + slot) * P.nib;
+    uint8_t *dst = P.enc + ((int64_t)p * P.n_eslots + eslot) * P.nib;
     for (int b = 0; b < P.nib; ++b) dst[b] = (uint8_t)(x >> (8 * b));
-    P.pbits[gid] = patches;
   }
-  // patches per unit = sum over the 32 lanes that share it (n_slots is a multiple of 32)
-  int cnt = __builtin_popcountll(patches);
-#pragma unroll
-  for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_down(cnt, o, 32);
-  if (valid && (tid & 31) == 0) P.counts[gid >> 5] = (uint32_t)cnt;
 }
 
 // exclusive scan of counts[0..n) into off[0..n], one workgroup
@@ -136,12 +143,12 @@ __global__ __launch_bounds__(ENC_THREADS) void emit_patches_kernel(const uint64_
 
 }  // namespace
 
-extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, const uint32_t *M_rows,
+extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *M_rows,
                                  const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
                                  uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity,
                                  void *workspace, int64_t workspace_bytes, void *hip_stream) {
   xorenc_sizes sz;
-  const int32_t rc = xorenc_get_sizes(m, n, n_in, q, &sz);
+  const int32_t rc = xorenc_get_sizes(m, n, n_in, q, n_out, &sz);
   if (rc != XORENC_OK) return rc;
   if (!M_rows || !mask || !planes || !enc_out || !patch_off_out || !workspace || patch_capacity < 0)
     return XORENC_EINVAL;
@@ -160,17 +167,24 @@ extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, 
   P.pbits = static_cast<uint64_t *>(workspace);
   P.counts = reinterpret_cast<uint32_t *>(static_cast<uint64_t *>(workspace) + total);
   P.n_slots = sz.n_slots;
+  P.n_eslots = sz.n_eslots;
   P.n_units = (int32_t)sz.n_units;
   P.n_in = n_in;
   P.nib = n_in / 8;
   P.q = q;
-  for (int i = 0; i < 64; ++i) {
+  P.J = n_out / 64;
+  P.spr = (int32_t)sz.spr;
+  P.espr = (int32_t)sz.espr;
+  for (int i = 0; i < XORENC_MAX_N_OUT; ++i) P.M_rows[i] = 0;
+  for (int i = 0; i < n_out; ++i) {
     if (n_in < 32 && (M_rows[i] >> n_in)) return XORENC_EINVAL;
     P.M_rows[i] = M_rows[i];
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int64_t slices = (int64_t)q * sz.n_eslots;
+  const unsigned eblocks = (unsigned)((slices + ENC_THREADS - 1) / ENC_THREADS);
   const unsigned blocks = (unsigned)((total + ENC_THREADS - 1) / ENC_THREADS);
-  hipLaunchKernelGGL(encode_slices_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, P);
+  hipLaunchKernelGGL(encode_slices_kernel, dim3(eblocks), dim3(ENC_THREADS), 0, st, P);
   hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, P.counts, patch_off_out, (int)n_counts);
   hipLaunchKernelGGL(emit_patches_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, P.pbits, patch_off_out, patch_out,
                      patch_capacity, total);

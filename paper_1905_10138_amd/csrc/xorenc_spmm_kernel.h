@@ -74,9 +74,10 @@ struct BoolC {
 };
 
 // NIBT = n_in/8 known at compile time (1..4), or 0: read it from the layer at run time.
+// JT = most 64-bit words per slice the variant has table space for: 1 (n_out = 64) or 4 (n_out up to 256).
 // PD = slice buffers per wave on the direct path: 2 (loads a slice and a half ahead, two waves per
 // SIMD hide each other's waits) or 1 (loads one slice ahead, more waves per SIMD do the hiding).
-template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT>
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
 __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
                                                       int use_atomic) {
@@ -101,7 +102,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   constexpr int TILE = CW * TS;                // a tile is stored column-major: [column][row]
   // The epilogue keeps NREG reduction tiles in LDS (over the then idle X buffers): as many as fit
   // next to the tables, at most one per wave, and a divisor of NW so that the rounds are even.
-  constexpr int FIT = (148 * 1024) / (TILE * 4);
+  constexpr int TILE_BUDGET = (JT == 1) ? 148 * 1024 : 160 * 1024 - 2048 - JT * NIBMAX * 2048;
+  constexpr int FIT = TILE_BUDGET / (TILE * 4);
   constexpr int NREG = largest_divisor_at_most(NW, FIT < 8 ? FIT : 8);
   constexpr int LDSB = (NW * XBUF > NREG * TILE * 4) ? NW * XBUF : NREG * TILE * 4;
   static_assert(!XF32 || NCB % 3 == 0, "fp32 X uses three bf16 terms per column");
@@ -110,9 +112,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   __shared__ __attribute__((aligned(16))) uint8_t xbuf_all[LDSB];
   // Small tables are kept once per wave (no workgroup barrier before the first look-up); larger
   // ones are shared by the workgroup.
-  constexpr bool PRIV_LUT = NIBT >= 1 && LDSB + NW * NIBT * 2048 + Q * ROWS * 4 <= 160 * 1024;
-  __shared__ uint32_t lut_all[(PRIV_LUT ? NW : 1) * NIBMAX * 512];
-  uint32_t *const lut = lut_all + (PRIV_LUT ? (threadIdx.x >> 6) * NIBMAX * 512 : 0);
+  constexpr bool PRIV_LUT = JT == 1 && NIBT >= 1 && LDSB + NW * NIBT * 2048 + Q * ROWS * 4 <= 160 * 1024;
+  constexpr int LUT_WORD = NIBMAX * 512;  // dwords of the tables of one 64-bit word of a slice
+  __shared__ uint32_t lut_all[(PRIV_LUT ? NW : 1) * JT * LUT_WORD];
+  uint32_t *const lut = lut_all + (PRIV_LUT ? (threadIdx.x >> 6) * LUT_WORD : 0);
+  static_assert(LDSB + (PRIV_LUT ? NW : 1) * JT * LUT_WORD * 4 + Q * ROWS * 4 <= 160 * 1024, "LDS budget");
   __shared__ __attribute__((aligned(16))) float alpha_s[Q * ROWS];
 
   // Every kernel argument the kernel uses is fetched up front in one batch of scalar loads (one
@@ -124,6 +128,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const float *const l_alpha = L.alpha;
   const int l_m = L.m, l_n = L.n, l_spr = L.spr, l_nrb = L.nrb, l_n_units = L.n_units, l_nib = L.nib, l_q = L.q;
   const int64_t l_n_slots = L.n_slots;
+  const int l_J = (JT > 1) ? L.J : 1, l_espr = (JT > 1) ? L.espr : L.spr;
+  const int64_t l_n_eslots = (JT > 1) ? L.n_eslots : L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
                "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_nib), "s"(l_q), "s"(l_n_slots), "s"(Xv), "s"(ldx), "s"(B),
                "s"(Y), "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
@@ -155,7 +161,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint32_t *>(l_mask32), 0, (uint32_t)(l_n_slots * 8), kRsrcFlags);
   const __amdgpu_buffer_rsrc_t ersrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t *>(l_enc), 0, (uint32_t)(l_n_slots * l_q * nib), kRsrcFlags);
+      const_cast<uint8_t *>(l_enc), 0, (uint32_t)(l_n_eslots * l_q * nib), kRsrcFlags);
 
   // ---- X loader.  One slice = 64 rows of X.  Chunk = 16 bytes of a row (8 bf16 / 4 fp32 columns).
   // XFAST: chunk i of a lane is (row i*RPI + lane/NCH, chunk lane%NCH), 16-byte loads.
@@ -285,10 +291,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       for (int p = 0; p < Q; ++p) c.e0[rb][p] = c.e1[rb][p] = 0u;
       if (rbg < l_nrb) {  // uniform
         const uint32_t u = (uint32_t)(rbg * l_spr + s);  // uniform
+        const uint32_t eu = (JT > 1) ? (uint32_t)(rbg * l_espr + s / l_J) : u;  // the unit's slices
         c.mw[rb] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_lane_off, u * 256u, 0);
 #pragma unroll
         for (int p = 0; p < Q; ++p) {
-          const uint32_t so = ((uint32_t)p * (uint32_t)l_n_slots + u * 32u) * (uint32_t)nib;
+          const uint32_t so = ((uint32_t)p * (uint32_t)l_n_eslots + eu * 32u) * (uint32_t)nib;
           c.e0[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so, 0);
           if (two_dw) c.e1[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so + 4u, 0);
         }
@@ -307,7 +314,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
                        kRsrcFlags};
   const u32x4 edesc = {(uint32_t)reinterpret_cast<uint64_t>(l_enc),
                        (uint32_t)(reinterpret_cast<uint64_t>(l_enc) >> 32) & 0xffffu,
-                       (uint32_t)(l_n_slots * l_q * nib), kRsrcFlags};
+                       (uint32_t)(l_n_eslots * l_q * nib), kRsrcFlags};
   constexpr int NGRP = NCH + KC;  // loads per slice
   uint32_t *const cbuf = reinterpret_cast<uint32_t *>(xbuf + (XDIR ? PD * XSL : 0));  // after the X slices
   const uint32_t cbuf_lds = __builtin_amdgcn_readfirstlane(
@@ -323,10 +330,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const uint32_t u = (uint32_t)((blockIdx.x * RB + rb) * l_spr + s);  // uniform
+      const uint32_t eu = (JT > 1) ? (uint32_t)((blockIdx.x * RB + rb) * l_espr + s / l_J) : u;
       dma_dword(cbuf_lds + (k++) * 256, m_lane_off, mdesc, u * 256u);
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
-        const uint32_t so = ((uint32_t)p * (uint32_t)l_n_slots + u * 32u) * (uint32_t)nib;
+        const uint32_t so = ((uint32_t)p * (uint32_t)l_n_eslots + eu * 32u) * (uint32_t)nib;
         dma_dword(cbuf_lds + (k++) * 256, e_lane_off, edesc, so);
         if (two_dw) dma_dword(cbuf_lds + (k++) * 256, e_lane_off, edesc, so + 4u);
       }
@@ -413,18 +421,19 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       }
     }
   } else {
-    for (int b = 0; b < nib; ++b)  // uniform
-      for (int v = tid; v < 256; v += NW * 64) {
-        uint32_t lo = 0, hi = 0;
+    for (int w = 0; w < l_J; ++w)      // uniform
+      for (int b = 0; b < nib; ++b)    // uniform
+        for (int v = tid; v < 256; v += NW * 64) {
+          uint32_t lo = 0, hi = 0;
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
-          if ((v >> t) & 1) {
-            lo ^= L.Mcol_lo[8 * b + t];
-            hi ^= L.Mcol_hi[8 * b + t];
-          }
-        lut[2 * (b * 256 + v)] = lo;
-        lut[2 * (b * 256 + v) + 1] = hi;
-      }
+          for (int t = 0; t < 8; ++t)
+            if ((v >> t) & 1) {
+              lo ^= L.Mcol_lo[w * XORENC_MAX_N_IN + 8 * b + t];
+              hi ^= L.Mcol_hi[w * XORENC_MAX_N_IN + 8 * b + t];
+            }
+          lut[w * LUT_WORD + 2 * (b * 256 + v)] = lo;
+          lut[w * LUT_WORD + 2 * (b * 256 + v) + 1] = hi;
+        }
   }
   for (int i = tid; i < Q * ROWS; i += NW * 64) {  // read only after the barrier that follows the loop
     const int p = i / ROWS, r = row0 + i % ROWS;
@@ -473,11 +482,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       tr_off[cb] = (uint32_t)(pos_lane * RSB + ((c ^ swz_of_pos(pos_lane)) * 16) + 8 * (c4 & 1));
     }
   }
-  const uint32_t *lut_g = lut + g;
+  const uint32_t *lut_g0 = lut + g;
   const uint32_t lane_id5 = (uint32_t)(rl * 2 + g);  // (row, half) as it appears in a patch entry
 
   // table look-ups of one slice: S[rb][p] = sign half-word of this lane (before patches)
-  auto lookup = [&](const Comp &c, uint32_t(&S)[RB][Q]) {
+  auto lookup = [&](const Comp &c, uint32_t(&S)[RB][Q], int s) {
+    // word s of a row is word s % J of its slice: that word's tables
+    const uint32_t *lut_g = lut_g0 + ((JT > 1) ? (s % l_J) * LUT_WORD : 0);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -563,7 +574,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t], 0);
-    lookup(ring[0], Snext);
+    lookup(ring[0], Snext, w0);
     if constexpr (XDIR && PD == 1) {
       if (cnt > 1) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the buffers have been read out
@@ -644,7 +655,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
             wait_loads(false);
             __builtin_amdgcn_sched_barrier(0);
             read_comp(0, ring[d ^ 1]);
-            lookup(ring[d ^ 1], Snext);
+            lookup(ring[d ^ 1], Snext, s + 1);
 #pragma unroll
             for (int t = 0; t < 4; ++t) read_bfrag(t, bfrag[t], 0);
             if (s + 2 < w1) {
@@ -674,7 +685,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
           __builtin_amdgcn_sched_barrier(0);
           if (has_next) {
             read_comp(d ^ 1, ring[d ^ 1]);
-            lookup(ring[d ^ 1], Snext);
+            lookup(ring[d ^ 1], Snext, s + 1);
             read_bfrag(0, bfrag[0], d ^ 1);
             read_bfrag(1, bfrag[1], d ^ 1);
           }
@@ -700,7 +711,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
           mfma_step(3);
           if (has_next) {
             read_bfrag(3, bfrag[3], d ^ 1);
-            lookup(ring[d ^ 1], Snext);
+            lookup(ring[d ^ 1], Snext, s + 1);
           }
         }
       }
@@ -796,16 +807,16 @@ static __global__ void zero_rows_kernel(float *Y, int64_t ldy, int m, int B) {
   if (i < (int64_t)m * B) Y[(i / B) * ldy + (i % B)] = 0.f;
 }
 
-template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT>
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
 inline void launch_variant(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, dim3 grid,
                            int sps, int atomic, hipStream_t st) {
-  hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, XFAST, PD, NIBT>), grid, dim3(NW * 64), 0, st, D, X, ldx, B,
+  hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, XFAST, PD, NIBT, JT>), grid, dim3(NW * 64), 0, st, D, X, ldx, B,
                      Y, ldy, sps, atomic);
 }
 
 // XMODE: 0 = the call site may see either layout, 1 = aligned X only, 2 = generic X only (keeps
 // variants that are never launched from being compiled)
-template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2, int XMODE = 0>
+template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2, int XMODE = 0, int JMODE = 0>
 int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, int x_fast,
                     hipStream_t st) {
   constexpr int NR = XF32 ? (32 * NCB) / 3 : 32 * NCB;
@@ -828,20 +839,35 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
   }
   const dim3 grid(row_groups, col_groups, ks);
   const int atomic = ks > 1 ? 1 : 0;
+  // JMODE: 1 = slices of one 64-bit word only, 4 = up to four words (more table space), 0 = both
+  if (D.J > 1 && JMODE == 1) return XORENC_EUNSUPPORTED;
+  const bool wide = (JMODE == 4) || (JMODE == 0 && D.J > 1);
   if (!x_fast) {
-    if constexpr (XMODE != 1)
-      launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
-    else
+    if constexpr (XMODE != 1) {
+      if constexpr (JMODE != 1)
+        if (wide) launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+      if constexpr (JMODE != 4)
+        if (!wide) launch_variant<NCB, Q, RB, XF32, NW, false, 1, 0, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+    } else {
       return XORENC_EUNSUPPORTED;
+    }
   } else if constexpr (XMODE == 2) {
     return XORENC_EUNSUPPORTED;
   } else {
-    switch (D.nib) {
-      case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-      case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-      case 3: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-      default: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-    }
+    if constexpr (JMODE != 1)
+      if (wide) switch (D.nib) {
+          case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 3: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          default: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4, 4>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+        }
+    if constexpr (JMODE != 4)
+      if (!wide) switch (D.nib) {
+          case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 3: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          default: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+        }
   }
   return xorenc_internal_check_launch();
 }
@@ -865,12 +891,15 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     }
     if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
-    if ((int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
-      return launch_spmm<2, Q, 4, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (D.J == 1 && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
+      return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
-    return launch_spmm<2, Q, 1, false>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (!x_fast) return launch_spmm<2, Q, 1, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
+    // two slice buffers per wave leave no room for the tables of multi-word slices
+    if (D.J > 1) return launch_spmm<2, Q, 1, false, 8, 1, 1, 4>(D, X, ldx, B, Y, ldy, x_fast, st);
+    return launch_spmm<2, Q, 1, false, 8, 2, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 3) {
     return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else {

@@ -395,12 +395,12 @@ int32_t launch_small(const DevLayer &D, const void *X, int64_t ldx, int B, float
 }
 
 // Tile shapes per Q: Q*RB accumulator sets of 16 registers; 16 / 12 / 8 waves leave 128 / 168 / 256 registers each.
-// Used for bf16 X with few columns whenever the rows of X are not 16-byte aligned multiples of
+// Used for bf16 X with few columns and slices of one 64-bit word (n_out = 64) whenever the rows of X are not 16-byte aligned multiples of
 // eight columns (for those the direct-to-LDS kernel is as fast or faster).
 template <int Q>
 bool dispatch_small_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
                       int x_fast, hipStream_t st, int32_t *rc) {
-  if (x_dtype != XORENC_X_BF16 || x_fast) return false;
+  if (x_dtype != XORENC_X_BF16 || x_fast || D.J != 1) return false;
   constexpr int RB = (Q <= 3) ? 2 : 1;
   constexpr int NW = (Q == 1) ? 16 : (Q == 2 ? 12 : 8);
   int ks = 1, sps = 0;

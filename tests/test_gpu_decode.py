@@ -13,9 +13,14 @@ FULL = [("fig1", None, None), ("fc6", None, None), ("lstm", None, None), ("large
         ("large_q2", None, None)]
 
 
-def _gpu_layer(name, m, n):
+# slices of two, three and four 64-bit words: (name, m, n, n_out, n_in)
+WIDE = [("lstm", 130, 3000, 192, 24), ("large_q1", 320, 1024, 128, 8), ("large_q2", 96, 4096, 256, 16),
+        ("fig1", 200, 448, 256, 32), ("tiny", 33, 70, 128, 16)]
+
+
+def _gpu_layer(name, m, n, n_out=None, n_in=None):
     import torch
-    wl, enc = encoded_workload(name, m, n)
+    wl, enc = encoded_workload(name, m, n, n_out=n_out, n_in=n_in)
     return wl, enc, pack_encoded(enc).to(torch.device("cuda:0"))
 
 
@@ -42,6 +47,23 @@ def test_dense_f32_and_bf16_bit_exact(name, m, n):
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
     got16 = xe.decode(L, xe.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
     assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(want))
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in", WIDE)
+def test_wide_slices_planes_and_dense_bit_exact(name, m, n, n_out, n_in):
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc, L = _gpu_layer(name, m, n, n_out, n_in)
+    assert enc.n_out == n_out and enc.n_in == n_in
+    got = xe.decode(L, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
+    want = decoder.pack_planes_u64(decoder.masked_planes(enc))
+    assert np.array_equal(got, want)
+    assert np.array_equal(want, decoder.pack_planes_u64(wl.planes))
+    dense = decoder.dequantize_f32(enc)
+    got32 = xe.decode(L, xe.OUT_F32).cpu().numpy()
+    assert np.array_equal(got32.view(np.uint32), dense.view(np.uint32))
+    got16 = xe.decode(L, xe.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(dense))
 
 
 def test_dense_output_with_leading_dimension_leaves_padding_untouched():

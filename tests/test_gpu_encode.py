@@ -13,21 +13,25 @@ CASES = [("tiny", 256, 256), ("fig1", 200, 448), ("fc6", 97, 640), ("lstm", 130,
          ("large_q2", 96, 4096), ("tiny", 33, 70), ("fig1", None, None), ("lstm", None, None), ("large_q2", None, None)]
 
 
+WIDE = [("lstm", 130, 3000, 192, 24), ("large_q1", 320, 1024, 128, 8), ("large_q2", 96, 4096, 256, 16),
+        ("fig1", 200, 448, 256, 32), ("tiny", 33, 70, 128, 16)]
+
+
 def gpu_encode(wl):
     import torch
     import paper_1905_10138_amd as xe
     dev = torch.device("cuda:0")
-    mask = torch.from_numpy(xe.pack_bits(wl.keep[:, :wl.n]).view(np.int64)).to(dev)
-    planes = torch.from_numpy(np.stack([xe.pack_bits(wl.planes[p][:, :wl.n]) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
+    n_out = wl.cfg.n_out
+    mask = torch.from_numpy(xe.pack_bits(wl.keep[:, :wl.n], n_out).view(np.int64)).to(dev)
+    planes = torch.from_numpy(
+        np.stack([xe.pack_bits(wl.planes[p][:, :wl.n], n_out) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
     alpha = torch.from_numpy(wl.alpha).to(dev)
     M_rows = (wl.M.astype(np.uint64) << np.arange(wl.cfg.n_in, dtype=np.uint64)).sum(axis=1).astype(np.uint32)
-    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha)
+    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha, n_out=n_out)
 
 
-@pytest.mark.parametrize("name,m,n", CASES)
-def test_gpu_encoder_matches_algorithm1_oracle(name, m, n):
+def _check_against_oracle(wl, enc):
     import paper_1905_10138_amd as xe
-    wl, enc = encoded_workload(name, m, n)
     L = gpu_encode(wl)
     host = L.to_host()
     assert xe.check_packed(host) == 0
@@ -40,6 +44,18 @@ def test_gpu_encoder_matches_algorithm1_oracle(name, m, n):
     # and the round trip through the GPU decoder is lossless on every kept bit
     planes = xe.decode(L, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
     assert np.array_equal(planes, decoder.pack_planes_u64(wl.planes))
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in", WIDE)
+def test_gpu_encoder_wide_slices(name, m, n, n_out, n_in):
+    wl, enc = encoded_workload(name, m, n, n_out=n_out, n_in=n_in)
+    _check_against_oracle(wl, enc)
+
+
+@pytest.mark.parametrize("name,m,n", CASES)
+def test_gpu_encoder_matches_algorithm1_oracle(name, m, n):
+    wl, enc = encoded_workload(name, m, n)
+    _check_against_oracle(wl, enc)
 
 
 def test_patch_capacity_overflow_is_reported_and_retried():

@@ -15,10 +15,10 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 2e-3, "f32": 1e-5}
 
 
-def _run(name, m, n, B, dtype, ldx_pad=0, S=None):
+def _run(name, m, n, B, dtype, ldx_pad=0, S=None, n_out=None, n_in=None):
     import torch
     import paper_1905_10138_amd as xe
-    wl, enc = encoded_workload(name, m, n, S)
+    wl, enc = encoded_workload(name, m, n, S, n_out, n_in)
     L = pack_encoded(enc).to(torch.device("cuda:0"))
     stored, exact = draw_X(wl.n, B, dtype, wl.cfg.seed_X + 1000 * B)
     if dtype == "bf16":
@@ -87,6 +87,30 @@ def test_many_patches_per_unit(B, dtype):
 def test_patch_counts_from_none_to_a_dozen_per_unit(B):
     """Pruning rate 0.93: units without patches next to units with up to a dozen."""
     got, want = _run("large_q1", 320, 1024, B, "bf16", S=0.93)
+    assert rel_fro(got, want) <= TOL["bf16"]
+
+
+WIDE_CASES = [
+    ("lstm", 130, 3000, 192, 24, 1, "bf16"), ("lstm", 130, 3000, 192, 24, 32, "bf16"), ("lstm", 130, 3000, 192, 24, 40, "f32"),
+    ("large_q1", 320, 1024, 128, 8, 8, "bf16"), ("large_q1", 320, 1024, 128, 8, 64, "bf16"),
+    ("large_q1", 320, 1024, 128, 8, 256, "bf16"), ("large_q1", 320, 1024, 128, 8, 5, "bf16"),
+    ("large_q2", 96, 4096, 256, 16, 8, "bf16"), ("large_q2", 96, 4096, 256, 16, 200, "bf16"),
+    ("fig1", 200, 448, 256, 32, 64, "bf16"), ("fig1", 200, 448, 256, 32, 63, "bf16"), ("tiny", 33, 70, 128, 16, 8, "f32"),
+]
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,B,dtype", WIDE_CASES)
+def test_spmm_with_slices_of_several_words(name, m, n, n_out, n_in, B, dtype):
+    """n_out = 128, 192, 256: one encrypted vector feeds two to four 64-bit words of a row."""
+    got, want = _run(name, m, n, B, dtype, n_out=n_out, n_in=n_in)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL[dtype]
+
+
+def test_paper_region_full_size():
+    """The paper's best compression is near n_out = 200 with n_in = 20: the LSTM-shaped layer at
+    n_out = 192, n_in = 24, full size, fused product at B = 32."""
+    got, want = _run("lstm", None, None, 32, "bf16", n_out=192, n_in=24)
     assert rel_fro(got, want) <= TOL["bf16"]
 
 

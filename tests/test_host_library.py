@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
             "xorenc_check_packed", "xorenc_version", "xorenc_strerror", "xorenc_last_hip_error"} <= names
     for n in names:
         assert hasattr(lib, n), n
-    assert xe.version() >> 16 == 1
+    assert xe.version() >> 16 == 2
     assert "align" in xe.strerror(-3)
 
 
@@ -31,6 +31,13 @@ def test_sizes():
     assert (s["n_pad"], s["m_pad"], s["spr"]) == (3008, 6016, 47)
     assert s["n_slots"] == 6016 * 47 and s["n_units"] == 188 * 47
     assert s["enc_bytes"] == 3 * s["n_slots"] * 3 and s["patch_off_words"] == 3 * s["n_units"] + 1
+    s = xe.get_sizes(6000, 3000, 24, 3, 192)                     # slices of three 64-bit words
+    assert (s["n_pad"], s["spr"], s["espr"]) == (3072, 48, 16)
+    assert s["n_eslots"] == 6016 * 16 and s["enc_bytes"] == 3 * s["n_eslots"] * 3
+    for bad in [(8, 8, 8, 1, 96), (8, 8, 8, 1, 320), (8, 8, 8, 1, 0)]:
+        with pytest.raises(xe.XorencError) as e:
+            xe.get_sizes(*bad)
+        assert e.value.code == -2
     for bad in [(0, 8, 8, 1), (8, 0, 8, 1)]:
         with pytest.raises(xe.XorencError) as e:
             xe.get_sizes(*bad)
@@ -41,25 +48,31 @@ def test_sizes():
         assert e.value.code == -2
 
 
-@pytest.mark.parametrize("name,m,n", [("tiny", 70, 256), ("lstm", 45, 200), ("large_q2", 64, 512), ("fc6", 33, 130)])
-def test_pack_unpack_roundtrip(name, m, n):
-    wl, enc = encoded_workload(name, m, n)
+@pytest.mark.parametrize("name,m,n,n_out", [("tiny", 70, 256, 64), ("lstm", 45, 200, 64), ("large_q2", 64, 512, 64),
+                                             ("fc6", 33, 130, 64), ("lstm", 45, 200, 192), ("large_q2", 64, 500, 128),
+                                             ("fig1", 40, 700, 256)])
+def test_pack_unpack_roundtrip(name, m, n, n_out):
+    wl, enc = encoded_workload(name, m, n, n_out=n_out)
     w_c, keep, n_patch, d_patch, M_rows = paper_format_arrays(enc)
     L = pack_encoded(enc)
     assert xe.check_packed(L) == 0
     w2, k2, np2, dp2 = xe.unpack(L)
     assert np.array_equal(w2, w_c) and np.array_equal(k2, keep)
     assert np.array_equal(np2, n_patch) and np.array_equal(dp2, d_patch)
-    # layout spot checks straight from the documented slot formula
+    # layout spot checks straight from the documented slot formulas
+    J = n_out // 64
     spr = wl.n_pad // 64
+    espr = wl.n_pad // n_out
+    n_eslots = L.mask.size // J
     nib = enc.n_in // 8
     rng = np.random.default_rng(0)
     for _ in range(50):
         r, s, p = rng.integers(m), rng.integers(spr), rng.integers(enc.q)
         slot = ((r // 32) * spr + s) * 32 + r % 32
         assert L.mask[slot] == keep[r * spr + s]
-        got = int.from_bytes(L.enc[(p * L.mask.size + slot) * nib:(p * L.mask.size + slot + 1) * nib].tobytes(), "little")
-        assert got == w_c[p, r * spr + s]
+        eslot = ((r // 32) * espr + s // J) * 32 + r % 32
+        got = int.from_bytes(L.enc[(p * n_eslots + eslot) * nib:(p * n_eslots + eslot + 1) * nib].tobytes(), "little")
+        assert got == w_c[p, r * espr + s // J]
     assert int(L.patch_off[-1]) == d_patch.size
     assert np.all(np.diff(L.patch_off.astype(np.int64)) >= 0)
 
@@ -107,7 +120,7 @@ def test_gpu_entry_points_validate_before_touching_the_gpu():
     assert lib.xorenc_decode(ctypes.byref(st), 0, out.ctypes.data + 4, 0, None) == -3
     bad = L.c_struct(); bad.struct_size = 8
     assert lib.xorenc_decode(ctypes.byref(bad), 0, out.ctypes.data, 0, None) == -1
-    bad = L.c_struct(); bad.n_out = 128
+    bad = L.c_struct(); bad.n_out = 96
     assert lib.xorenc_decode(ctypes.byref(bad), 0, out.ctypes.data, 0, None) == -2
     bad = L.c_struct(); bad.q = 9
     assert lib.xorenc_spmm(ctypes.byref(bad), out.ctypes.data, 1, 8, 8, out.ctypes.data, 8, None) == -2
