@@ -42,6 +42,7 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of W in the CPU-oracle sample (0 = auto)")
     ap.add_argument("--replica-bytes", type=float, default=float(1 << 30))
     ap.add_argument("--decode-only", action="store_true", help="also time xorenc_decode (planes) on the workload")
+    ap.add_argument("--no-wide", action="store_true", help="skip the n_out=192 / n_in=24 extra on the same matrix")
     ap.add_argument("--no-fig1", action="store_true", help="skip the Fig. 1-shaped extra (decode-only and fused, B=64)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region run one 256 MiB device copy (reference dispatch for rocprofv3 --pmc)")
@@ -50,17 +51,18 @@ def parse_args():
 
 def build_layer(wl, xe, torch, dev):
     """Encode the workload on the GPU (xorenc_encode) and return the device layer."""
-    mask = torch.from_numpy(xe.pack_bits(wl.keep[:, :wl.n]).view(np.int64)).to(dev)
+    n_out = wl.cfg.n_out
+    mask = torch.from_numpy(xe.pack_bits(wl.keep[:, :wl.n], n_out).view(np.int64)).to(dev)
     planes = torch.from_numpy(
-        np.stack([xe.pack_bits(wl.planes[p][:, :wl.n]) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
+        np.stack([xe.pack_bits(wl.planes[p][:, :wl.n], n_out) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
     alpha = torch.from_numpy(wl.alpha).to(dev)
     M_rows = (wl.M.astype(np.uint64) << np.arange(wl.cfg.n_in, dtype=np.uint64)).sum(axis=1).astype(np.uint32)
-    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha)
+    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha, n_out=n_out)
 
 
 def clone_layer(L, xe):
     return xe.PackedLayer(L.m, L.n, L.n_in, L.q, L.M_rows, L.enc.clone(), L.mask.clone(), L.patch_off.clone(),
-                          L.patch.clone(), L.alpha.clone())
+                          L.patch.clone(), L.alpha.clone(), L.n_out)
 
 
 class SpmmRunner:
@@ -215,6 +217,32 @@ def fig1_extra(xe, torch, dev, args):
     return res
 
 
+def wide_extra(xe, torch, dev, args, base_cfg):
+    """The default workload re-encoded with slices of 192 bits and n_in = 24 (the region where the paper
+    reports its best ratios, Section 3.3): same bits per weight for the encrypted stream, fewer patches."""
+    import dataclasses
+
+    from synth_inputs import make_workload
+    cfg = dataclasses.replace(base_cfg, n_out=192, n_in=24)
+    wl = make_workload(cfg)
+    layer = build_layer(wl, xe, torch, dev)
+    res = {"workload": f"{cfg.name}: W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in=24 n_out=192 bf16",
+           "compressed_bytes": layer.compressed_bytes(), "patches": int(layer.patch.numel())}
+    for B in (8, 64):
+        stored, _ = wl.X(B)
+        xg = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev)
+        runner = SpmmRunner(xe, torch, layer, xg, B, args.replica_bytes)
+        if not args.no_graph:
+            runner.capture()
+        steps = max(200, args.sweep_steps)
+        wall, ev = runner.time(steps, 50)
+        res[f"B{B}_us_per_launch"] = ev * 1e6 / steps
+        res[f"B{B}_tflops"] = 2.0 * cfg.m * cfg.n * B * steps / wall / 1e12
+        res[f"B{B}_compressed_gbs"] = runner.comp_bytes * steps / wall / 1e9
+        del runner
+    return res
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -299,6 +327,8 @@ def main():
     }
     if not args.no_fig1 and cfg.name != "fig1":
         extra["fig1"] = fig1_extra(xe, torch, dev, args)
+    if not args.no_wide and cfg.n_out == 64:
+        extra["n_out_192"] = wide_extra(xe, torch, dev, args, cfg)
     if args.copy_calibration:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)
