@@ -86,6 +86,39 @@ def encode_plane(care: np.ndarray, bits: np.ndarray, M: np.ndarray):
     return w_c, n_patch, d_patch
 
 
+def encode_plane_exhaustive(care: np.ndarray, bits: np.ndarray, M: np.ndarray):
+    """Section 5.2 (minimising n_patch for small n_in): list all 2^n_in inputs with their outputs
+    through the XOR-gate network and keep, per slice, an input with the fewest mismatched care
+    bits; among those the smallest one as an integer (bit j = x_j).  Same return value as
+    `encode_plane`.  Work grows as l * 2^n_in * n_out: meant for n_in <= 16."""
+    M = np.asarray(M, dtype=np.uint8)
+    n_out, n_in = M.shape
+    if n_in > 16:
+        raise ValueError("exhaustive search is limited to n_in <= 16")
+    xs = ((np.arange(1 << n_in)[:, None] >> np.arange(n_in)) & 1).astype(np.uint8)
+    ys = xor_network(M, xs).astype(bool)                         # (2^n_in, n_out): every output
+    care = np.asarray(care, dtype=bool)
+    bits = np.asarray(bits, dtype=bool)
+    l = care.shape[0]
+    w_c = np.zeros((l, n_in), dtype=np.uint8)
+    mism = np.zeros((l, n_out), dtype=bool)
+    step = max(1, (1 << 22) >> n_in)                             # slices per chunk
+    ysf = ys.astype(np.float64)
+    for a in range(0, l, step):
+        c = care[a:a + step]
+        t = bits[a:a + step] & c
+        # mismatches of input v on slice s = sum over care bits of (y_v xor t_s)
+        #   = sum_i c_si y_vi + sum_i t_si - 2 sum_i t_si y_vi   (t is zero outside the care set);
+        # small integers, exact in float64
+        dist = (c.astype(np.float64) - 2.0 * t.astype(np.float64)) @ ysf.T + t.sum(axis=1)[:, None]
+        best = np.argmin(dist, axis=1)                           # first minimum = smallest integer
+        w_c[a:a + step] = xs[best]
+        mism[a:a + step] = c & (ys[best] != bits[a:a + step])
+    n_patch = mism.sum(axis=1).astype(np.int32)
+    d_patch = np.nonzero(mism)[1].astype(np.int64)
+    return w_c, n_patch, d_patch
+
+
 @dataclass
 class Encoded:
     """The compressed format of Section 3.2 for one weight matrix (all bit-planes)."""
@@ -107,18 +140,21 @@ class Encoded:
         return self.m * self.n_pad // self.n_out
 
 
-def encode(keep: np.ndarray, planes: np.ndarray, alpha: np.ndarray, M: np.ndarray, n: int) -> Encoded:
+def encode(keep: np.ndarray, planes: np.ndarray, alpha: np.ndarray, M: np.ndarray, n: int,
+           exhaustive: bool = False) -> Encoded:
     """Encrypt all bit-planes of a pruned, binary-coded matrix.
 
     keep: bool (m, n_pad); planes: bool (q, m, n_pad); alpha: float32 (q, m); n: real column count.
+    exhaustive: the 2^n_in search of Section 5.2 in place of Algorithm 1.
     """
     M = np.asarray(M, dtype=np.uint8)
     n_out, n_in = M.shape
     q, m, n_pad = planes.shape
     care = slice_plane(keep, n_out)
     w_c, n_patch, d_patch = [], [], []
+    one_plane = encode_plane_exhaustive if exhaustive else encode_plane
     for p in range(q):
-        wc, npch, dp = encode_plane(care, slice_plane(planes[p], n_out), M)
+        wc, npch, dp = one_plane(care, slice_plane(planes[p], n_out), M)
         w_c.append(wc)
         n_patch.append(npch)
         d_patch.append(dp)

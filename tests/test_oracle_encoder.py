@@ -206,3 +206,27 @@ def test_flipping_is_an_involution():
     spr = wl.n_pad // 64
     assert not e2.w_c[:, 3 * spr:(3 + 1) * spr].any()
     assert not e2.n_patch[:, 3 * spr:(3 + 1) * spr].any()
+
+
+@pytest.mark.parametrize("n_out,n_in,p_care", [(64, 8, 0.1), (64, 8, 0.3), (128, 10, 0.08), (192, 12, 0.06)])
+def test_vectorised_exhaustive_search_against_the_per_slice_listing(n_out, n_in, p_care):
+    """`encode_plane_exhaustive` (all slices at once, distances through a matrix product) against
+    `patch_search.exhaustive_min_patches` (one slice, mismatches counted directly): same minimum, same
+    input (both take the first minimum in integer order), never more patches than Algorithm 1, and the
+    patched output reproduces every care bit."""
+    rng = np.random.default_rng(7 * n_out + n_in)
+    M = rng.integers(0, 2, size=(n_out, n_in), dtype=np.uint8)
+    l = 60
+    care = rng.random((l, n_out)) < p_care
+    bits = rng.integers(0, 2, size=(l, n_out)).astype(bool) & care
+    w_c, n_patch, d_patch = encoder.encode_plane_exhaustive(care, bits, M)
+    _, n_g, _ = encoder.encode_plane(care, bits, M)
+    assert np.all(n_patch <= n_g)
+    pos = np.split(d_patch, np.cumsum(n_patch)[:-1])
+    for s in range(l):
+        opt, x_opt = patch_search.exhaustive_min_patches(care[s], bits[s], M)
+        assert n_patch[s] == opt
+        assert np.array_equal(w_c[s], x_opt)
+        y = gf2.xor_network(M, w_c[s][None])[0].astype(bool)
+        y[pos[s]] ^= True
+        assert np.array_equal(y & care[s], bits[s])
