@@ -43,21 +43,28 @@ def parse_args():
     ap.add_argument("--replica-bytes", type=float, default=float(1 << 30))
     ap.add_argument("--decode-only", action="store_true", help="also time xorenc_decode (planes) on the workload")
     ap.add_argument("--no-wide", action="store_true", help="skip the n_out=192 / n_in=24 extra on the same matrix")
+    ap.add_argument("--no-encoder", action="store_true", help="skip the timing of the two GPU encoders")
     ap.add_argument("--no-fig1", action="store_true", help="skip the Fig. 1-shaped extra (decode-only and fused, B=64)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region run one 256 MiB device copy (reference dispatch for rocprofv3 --pmc)")
     return ap.parse_args()
 
 
-def build_layer(wl, xe, torch, dev):
-    """Encode the workload on the GPU (xorenc_encode) and return the device layer."""
+def encoder_inputs(wl, xe, torch, dev):
+    """Unit-major mask and bit-planes of the workload on the GPU, alpha, and the rows of M as integers."""
     n_out = wl.cfg.n_out
     mask = torch.from_numpy(xe.pack_bits(wl.keep[:, :wl.n], n_out).view(np.int64)).to(dev)
     planes = torch.from_numpy(
         np.stack([xe.pack_bits(wl.planes[p][:, :wl.n], n_out) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
     alpha = torch.from_numpy(wl.alpha).to(dev)
     M_rows = (wl.M.astype(np.uint64) << np.arange(wl.cfg.n_in, dtype=np.uint64)).sum(axis=1).astype(np.uint32)
-    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha, n_out=n_out)
+    return mask, planes, alpha, M_rows
+
+
+def build_layer(wl, xe, torch, dev):
+    """Encode the workload on the GPU (xorenc_encode) and return the device layer."""
+    mask, planes, alpha, M_rows = encoder_inputs(wl, xe, torch, dev)
+    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha, n_out=wl.cfg.n_out)
 
 
 def clone_layer(L, xe):
@@ -243,6 +250,36 @@ def wide_extra(xe, torch, dev, args, base_cfg):
     return res
 
 
+def encoder_extra(xe, torch, dev, base_cfg):
+    """Both GPU encoders (Algorithm 1; the 2^n_in search of Section 5.2) on the default matrix, at its own
+    slice geometry and at n_out = 128 / n_in = 16.  Times are host wall-clock around the binding call
+    (buffer allocation, three kernels, one synchronisation to read the patch total), best of three."""
+    import dataclasses
+
+    from synth_inputs import make_workload
+    res = []
+    for n_out, n_in in ((base_cfg.n_out, base_cfg.n_in), (128, 16)):
+        cfg = dataclasses.replace(base_cfg, n_out=n_out, n_in=n_in)
+        if n_in > 16:
+            continue
+        wl = make_workload(cfg)
+        mask, planes, alpha, M_rows = encoder_inputs(wl, xe, torch, dev)
+        slices = cfg.q * wl.m * (-(-wl.n // n_out))
+        ent = {"n_out": n_out, "n_in": n_in, "slices": slices}
+        for key, fn in (("algorithm1", xe.encode), ("exhaustive", xe.encode_exhaustive)):
+            best = float("inf")
+            for _ in range(4):      # the first call warms up
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                L = fn(wl.m, wl.n, n_in, cfg.q, M_rows, mask, planes, alpha, n_out=n_out)
+                torch.cuda.synchronize()
+                best = min(best, time.perf_counter() - t0)
+            ent[key] = {"ms": best * 1e3, "patches": int(L.patch.numel())}
+        ent["exhaustive"]["inputs_tried_per_s"] = slices * float(1 << n_in) / (ent["exhaustive"]["ms"] * 1e-3)
+        res.append(ent)
+    return res
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -329,6 +366,8 @@ def main():
         extra["fig1"] = fig1_extra(xe, torch, dev, args)
     if not args.no_wide and cfg.n_out == 64:
         extra["n_out_192"] = wide_extra(xe, torch, dev, args, cfg)
+    if not args.no_encoder:
+        extra["encoder"] = encoder_extra(xe, torch, dev, cfg)
     if args.copy_calibration:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)

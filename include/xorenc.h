@@ -176,6 +176,21 @@ XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, 
                                  void *workspace, int64_t workspace_bytes, void *hip_stream);
 
 /*
+ * Encoder on the GPU with the fewest patches (Section 5.2, minimising n_patch for small n_in): for
+ * every slice all 2^n_in inputs of the XOR-gate network are tried and one whose output differs from
+ * the quantised bits on the fewest care positions is kept; among equals the smallest input read as
+ * an integer (bit j = x_j).  Patches are the remaining mismatches.  Arguments, outputs, workspace and
+ * stream behaviour exactly as xorenc_encode.  Work is l * 2^n_in per plane: XORENC_EUNSUPPORTED for
+ * n_in > XORENC_EXH_MAX_N_IN.
+ */
+#define XORENC_EXH_MAX_N_IN 16
+XORENC_API int32_t xorenc_encode_exhaustive(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                            const uint32_t *M_rows, const uint64_t *mask, const uint64_t *planes,
+                                            uint8_t *enc_out, uint32_t *patch_off_out, uint16_t *patch_out,
+                                            int64_t patch_capacity, void *workspace, int64_t workspace_bytes,
+                                            void *hip_stream);
+
+/*
  * Decode only (Sections 3.1-3.2 + mask + dequantisation).
  *   XORENC_OUT_PLANES: out = DEV uint64[q][m*spr], word p*(m*spr) + r*spr + s = decrypted, patched
  *                      64-bit word with pruned and padding positions forced to 0; ld_out ignored.

@@ -10,6 +10,7 @@ from .binding import (
     check_packed,
     decode,
     encode,
+    encode_exhaustive,
     get_sizes,
     library_path,
     load_library,
@@ -22,6 +23,7 @@ from .binding import (
 )
 
 __all__ = [
-    "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode", "encode", "pack_bits",
+    "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode", "encode", "encode_exhaustive",
+    "pack_bits",
     "get_sizes", "library_path", "load_library", "pack", "spmm", "strerror", "unpack", "version",
 ]

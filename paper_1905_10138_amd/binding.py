@@ -75,6 +75,8 @@ def load_library():
     lib.xorenc_pack_bits.argtypes = [i32, i32, i32, vp, i64, vp]
     lib.xorenc_encode.restype = i32
     lib.xorenc_encode.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    lib.xorenc_encode_exhaustive.restype = i32
+    lib.xorenc_encode_exhaustive.argtypes = lib.xorenc_encode.argtypes
     lib.xorenc_decode.restype = i32
     lib.xorenc_decode.argtypes = [ctypes.POINTER(_Layer), i32, vp, i64, vp]
     lib.xorenc_spmm.restype = i32
@@ -218,7 +220,7 @@ def pack_bits(a: np.ndarray, n_out: int = 64) -> np.ndarray:
 
 
 def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[int] = None,
-           n_out: int = 64) -> PackedLayer:
+           n_out: int = 64, _entry: str = "xorenc_encode") -> PackedLayer:
     """xorenc_encode on the current stream.  mask: int64 GPU tensor [n_slots] (unit-major words),
     planes: int64 GPU tensor [q, n_slots], alpha: float32 GPU tensor [q, m].  Returns a device
     PackedLayer that shares `mask` and `alpha`.  Synchronises once to read the patch total (the
@@ -237,15 +239,22 @@ def encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[
     cap = int(patch_capacity) if patch_capacity is not None else max(1024, q * sz["n_slots"] // 8)
     while True:
         patch = torch.empty(cap, dtype=torch.int16, device=dev)
-        _check(lib.xorenc_encode(m, n, n_in, q, n_out, _np_ptr(M_rows), ctypes.c_void_p(mask.data_ptr()),
-                                 ctypes.c_void_p(planes.data_ptr()), ctypes.c_void_p(enc.data_ptr()),
-                                 ctypes.c_void_p(patch_off.data_ptr()), ctypes.c_void_p(patch.data_ptr()), cap,
-                                 ctypes.c_void_p(ws.data_ptr()), ws.numel() * 8, _stream_ptr()), "xorenc_encode")
+        _check(getattr(lib, _entry)(m, n, n_in, q, n_out, _np_ptr(M_rows), ctypes.c_void_p(mask.data_ptr()),
+                                    ctypes.c_void_p(planes.data_ptr()), ctypes.c_void_p(enc.data_ptr()),
+                                    ctypes.c_void_p(patch_off.data_ptr()), ctypes.c_void_p(patch.data_ptr()), cap,
+                                    ctypes.c_void_p(ws.data_ptr()), ws.numel() * 8, _stream_ptr()), _entry)
         total = int(patch_off[-1].item())
         if total <= cap:
             break
         cap = total
     return PackedLayer(m, n, n_in, q, M_rows, enc, mask, patch_off, patch[:total], alpha, n_out)
+
+
+def encode_exhaustive(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity: Optional[int] = None,
+                      n_out: int = 64) -> PackedLayer:
+    """xorenc_encode_exhaustive on the current stream; arguments and result as `encode`."""
+    return encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity, n_out,
+                  _entry="xorenc_encode_exhaustive")
 
 
 def check_packed(layer: PackedLayer) -> int:

@@ -8,6 +8,12 @@
 // 1): then it is dropped and position i becomes a patch.  Otherwise it joins the basis.  After
 // the last care bit, back-substitution with every free variable 0 gives w^c, which is the
 // solution the reduced row-echelon form of the accepted rows yields.
+//
+// Second encoder (Section 5.2, minimising n_patch for small n_in): every one of the 2^n_in inputs is
+// tried on every slice and the one with the fewest mismatched care bits is kept.  All lanes walk the
+// inputs in the same (Gray code) order, so the output of the XOR-gate network for the current input
+// is wave-uniform and is kept up to date with one XOR of a column of M per step; a lane only counts
+// the mismatches on its own slice.  Ties go to the smallest input read as an integer.
 #include <hip/hip_runtime.h>
 
 #include "xorenc_internal.h"
@@ -92,6 +98,99 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_slices_kernel(EncParams P)
   }
 }
 
+struct ExhParams {
+  const uint64_t *mask;
+  const uint64_t *planes;
+  uint8_t *enc;
+  uint64_t *pbits;
+  uint32_t *counts;
+  int64_t n_slots, n_eslots;
+  int32_t n_units, n_in, nib, q, spr, espr;
+  uint64_t Mcol[XORENC_MAX_J][XORENC_EXH_MAX_N_IN];  // [w][j]: bit i = M[64 w + i][j]
+};
+
+template <int J>
+__global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParams P) {
+  const int tid = threadIdx.x;
+  const int64_t gid = (int64_t)blockIdx.x * ENC_THREADS + tid;
+  const int64_t total = (int64_t)P.q * P.n_eslots;
+  const bool valid = gid < total;
+  const int64_t eslot = valid ? gid % P.n_eslots : 0;
+  const int p = valid ? (int)(gid / P.n_eslots) : 0;
+  const int rr = (int)(eslot & 31);
+  const int64_t eu = eslot >> 5;
+  const int64_t rb = eu / P.espr, S = eu % P.espr;
+  const int64_t unit0 = rb * P.spr + S * J;
+
+  uint64_t care[J], want[J];
+#pragma unroll
+  for (int w = 0; w < J; ++w) {
+    const int64_t slot = (unit0 + w) * 32 + rr;
+    care[w] = valid ? P.mask[slot] : 0ull;
+    want[w] = valid ? (P.planes[(int64_t)p * P.n_slots + slot] & care[w]) : 0ull;
+  }
+  // wave-uniform state: the current input x and its output y
+  uint32_t x = 0;
+  uint64_t y[J], c0[J], c1[J], c2[J];
+#pragma unroll
+  for (int w = 0; w < J; ++w) {
+    y[w] = 0;
+    c0[w] = P.Mcol[w][0];
+    c1[w] = P.Mcol[w][1];
+    c2[w] = P.Mcol[w][2];
+  }
+  uint32_t best = 0xffffffffu;  // (mismatches << 16) | x: the minimum is the fewest patches, then the smallest x
+  auto flip = [&](int j, const uint64_t(&col)[J]) {
+    x ^= 1u << j;
+#pragma unroll
+    for (int w = 0; w < J; ++w) y[w] ^= col[w];
+  };
+  auto eval = [&]() {
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int w = 0; w < J; ++w) cnt += (uint32_t)__builtin_popcountll((y[w] & care[w]) ^ want[w]);
+    best = min(best, (cnt << 16) | x);
+  };
+  // Gray code walk: step k flips bit ctz(k); inside a group of 8 steps the flipped bits are
+  // 0 1 0 2 0 1 0, and only the step into the next group needs a column chosen at run time.
+  const uint32_t groups = (1u << P.n_in) >> 3;  // n_in >= 8
+  for (uint32_t g = 0; g < groups; ++g) {
+    if (g) {
+      const int j = __builtin_ctz(g) + 3;
+      uint64_t cj[J];
+#pragma unroll
+      for (int w = 0; w < J; ++w) cj[w] = P.Mcol[w][j];
+      flip(j, cj);
+    }
+    eval();
+    flip(0, c0); eval();
+    flip(1, c1); eval();
+    flip(0, c0); eval();
+    flip(2, c2); eval();
+    flip(0, c0); eval();
+    flip(1, c1); eval();
+    flip(0, c0); eval();
+  }
+  const uint32_t xb = best & 0xffffu;
+  // output of the chosen input, patches = mismatched care bits
+#pragma unroll
+  for (int w = 0; w < J; ++w) {
+    uint64_t yb = 0;
+    for (int j = 0; j < P.n_in; ++j) yb ^= ((xb >> j) & 1u) ? P.Mcol[w][j] : 0ull;
+    const uint64_t patches = (yb & care[w]) ^ want[w];
+    const int64_t slot = (unit0 + w) * 32 + rr;
+    if (valid) P.pbits[(int64_t)p * P.n_slots + slot] = patches;
+    int cnt = __builtin_popcountll(patches);
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_down(cnt, o, 32);
+    if (valid && rr == 0) P.counts[(int64_t)p * P.n_units + unit0 + w] = (uint32_t)cnt;
+  }
+  if (valid) {
+    uint8_t *dst = P.enc + ((int64_t)p * P.n_eslots + eslot) * P.nib;
+    for (int b = 0; b < P.nib; ++b) dst[b] = (uint8_t)(xb >> (8 * b));
+  }
+}
+
 // exclusive scan of counts[0..n) into off[0..n], one workgroup
 __global__ __launch_bounds__(1024) void scan_counts_kernel(const uint32_t *counts, uint32_t *off, int n) {
   __shared__ uint32_t part[1024];
@@ -143,16 +242,19 @@ __global__ __launch_bounds__(ENC_THREADS) void emit_patches_kernel(const uint64_
 
 }  // namespace
 
-extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *M_rows,
-                                 const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
-                                 uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity,
-                                 void *workspace, int64_t workspace_bytes, void *hip_stream) {
+namespace {
+
+int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                      const uint32_t *M_rows, const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
+                      uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity, void *workspace,
+                      int64_t workspace_bytes, void *hip_stream) {
   xorenc_sizes sz;
   const int32_t rc = xorenc_get_sizes(m, n, n_in, q, n_out, &sz);
   if (rc != XORENC_OK) return rc;
   if (!M_rows || !mask || !planes || !enc_out || !patch_off_out || !workspace || patch_capacity < 0)
     return XORENC_EINVAL;
   if (patch_capacity > 0 && !patch_out) return XORENC_EINVAL;
+  if (exhaustive && n_in > XORENC_EXH_MAX_N_IN) return XORENC_EUNSUPPORTED;
   const int64_t total = (int64_t)q * sz.n_slots;
   const int64_t n_counts = (int64_t)q * sz.n_units;
   if (workspace_bytes < total * 8 + n_counts * 4) return XORENC_EINVAL;
@@ -160,33 +262,83 @@ extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, 
   if (((uintptr_t)mask & 7) || ((uintptr_t)planes & 7) || ((uintptr_t)workspace & 7) ||
       ((uintptr_t)patch_off_out & 3) || ((uintptr_t)patch_out & 1))
     return XORENC_EALIGN;
-  EncParams P;
-  P.mask = mask;
-  P.planes = planes;
-  P.enc = enc_out;
-  P.pbits = static_cast<uint64_t *>(workspace);
-  P.counts = reinterpret_cast<uint32_t *>(static_cast<uint64_t *>(workspace) + total);
-  P.n_slots = sz.n_slots;
-  P.n_eslots = sz.n_eslots;
-  P.n_units = (int32_t)sz.n_units;
-  P.n_in = n_in;
-  P.nib = n_in / 8;
-  P.q = q;
-  P.J = n_out / 64;
-  P.spr = (int32_t)sz.spr;
-  P.espr = (int32_t)sz.espr;
-  for (int i = 0; i < XORENC_MAX_N_OUT; ++i) P.M_rows[i] = 0;
-  for (int i = 0; i < n_out; ++i) {
+  for (int i = 0; i < n_out; ++i)
     if (n_in < 32 && (M_rows[i] >> n_in)) return XORENC_EINVAL;
-    P.M_rows[i] = M_rows[i];
-  }
+  uint64_t *pbits = static_cast<uint64_t *>(workspace);
+  uint32_t *counts = reinterpret_cast<uint32_t *>(pbits + total);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int64_t slices = (int64_t)q * sz.n_eslots;
   const unsigned eblocks = (unsigned)((slices + ENC_THREADS - 1) / ENC_THREADS);
   const unsigned blocks = (unsigned)((total + ENC_THREADS - 1) / ENC_THREADS);
-  hipLaunchKernelGGL(encode_slices_kernel, dim3(eblocks), dim3(ENC_THREADS), 0, st, P);
-  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, P.counts, patch_off_out, (int)n_counts);
-  hipLaunchKernelGGL(emit_patches_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, P.pbits, patch_off_out, patch_out,
+  const int J = n_out / 64;
+  if (exhaustive) {
+    ExhParams P;
+    P.mask = mask;
+    P.planes = planes;
+    P.enc = enc_out;
+    P.pbits = pbits;
+    P.counts = counts;
+    P.n_slots = sz.n_slots;
+    P.n_eslots = sz.n_eslots;
+    P.n_units = (int32_t)sz.n_units;
+    P.n_in = n_in;
+    P.nib = n_in / 8;
+    P.q = q;
+    P.spr = (int32_t)sz.spr;
+    P.espr = (int32_t)sz.espr;
+    for (int w = 0; w < XORENC_MAX_J; ++w)
+      for (int j = 0; j < XORENC_EXH_MAX_N_IN; ++j) {
+        uint64_t col = 0;
+        if (w < J && j < n_in)
+          for (int i = 0; i < 64; ++i) col |= (uint64_t)((M_rows[64 * w + i] >> j) & 1u) << i;
+        P.Mcol[w][j] = col;
+      }
+    switch (J) {
+      case 1: hipLaunchKernelGGL(exhaustive_slices_kernel<1>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
+      case 2: hipLaunchKernelGGL(exhaustive_slices_kernel<2>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
+      case 3: hipLaunchKernelGGL(exhaustive_slices_kernel<3>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
+      default: hipLaunchKernelGGL(exhaustive_slices_kernel<4>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
+    }
+  } else {
+    EncParams P;
+    P.mask = mask;
+    P.planes = planes;
+    P.enc = enc_out;
+    P.pbits = pbits;
+    P.counts = counts;
+    P.n_slots = sz.n_slots;
+    P.n_eslots = sz.n_eslots;
+    P.n_units = (int32_t)sz.n_units;
+    P.n_in = n_in;
+    P.nib = n_in / 8;
+    P.q = q;
+    P.J = J;
+    P.spr = (int32_t)sz.spr;
+    P.espr = (int32_t)sz.espr;
+    for (int i = 0; i < XORENC_MAX_N_OUT; ++i) P.M_rows[i] = i < n_out ? M_rows[i] : 0u;
+    hipLaunchKernelGGL(encode_slices_kernel, dim3(eblocks), dim3(ENC_THREADS), 0, st, P);
+  }
+  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, counts, patch_off_out, (int)n_counts);
+  hipLaunchKernelGGL(emit_patches_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, pbits, patch_off_out, patch_out,
                      patch_capacity, total);
   return xorenc_internal_check_launch();
+}
+
+}  // namespace
+
+extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *M_rows,
+                                 const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,
+                                 uint32_t *patch_off_out, uint16_t *patch_out, int64_t patch_capacity,
+                                 void *workspace, int64_t workspace_bytes, void *hip_stream) {
+  return encode_common(false, m, n, n_in, q, n_out, M_rows, mask, planes, enc_out, patch_off_out, patch_out,
+                       patch_capacity, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int32_t xorenc_encode_exhaustive(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                            const uint32_t *M_rows, const uint64_t *mask, const uint64_t *planes,
+                                            uint8_t *enc_out, uint32_t *patch_off_out, uint16_t *patch_out,
+                                            int64_t patch_capacity, void *workspace, int64_t workspace_bytes,
+                                            void *hip_stream) {
+  return encode_common(true, m, n, n_in, q, n_out, M_rows, mask, planes, enc_out, patch_off_out, patch_out,
+                       patch_capacity, workspace, workspace_bytes, hip_stream);
 }

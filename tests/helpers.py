@@ -27,16 +27,17 @@ def pack_encoded(enc: "oenc.Encoded"):
 
 
 @functools.lru_cache(maxsize=8)
-def encoded_workload(name: str, m=None, n=None, S=None, n_out=None, n_in=None):
+def encoded_workload(name: str, m=None, n=None, S=None, n_out=None, n_in=None, exhaustive=False):
     """(workload, oracle-encoded) for a config, cached for the test session.  `S` overrides the
     pruning rate (a low rate with a small n_in gives many patches per slice); `n_out` / `n_in`
-    override the slice geometry (the paper's best ratios are at n_out near 200 with n_in = 20)."""
+    override the slice geometry (the paper's best ratios are at n_out near 200 with n_in = 20);
+    `exhaustive` encodes with the 2^n_in search of Section 5.2 in place of Algorithm 1."""
     cfg = CONFIGS[name]
     over = {k: v for k, v in (("S", S), ("n_out", n_out), ("n_in", n_in)) if v is not None}
     if over:
         cfg = dataclasses.replace(cfg, **over)
     wl = make_workload(cfg, m=m, n=n)
-    return wl, oenc.encode(wl.keep, wl.planes, wl.alpha, wl.M, wl.n)
+    return wl, oenc.encode(wl.keep, wl.planes, wl.alpha, wl.M, wl.n, exhaustive=exhaustive)
 
 
 def rel_fro(a, b) -> float:

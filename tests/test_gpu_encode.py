@@ -1,6 +1,8 @@
 """GPU encoder (xorenc_encode) against the oracle's Algorithm 1: encrypted bits and patch lists
 are unique under the stated readings (ascending care bits, free variables 0), so the comparison
-is bit-exact.  The decode of the GPU-encoded layer must also reproduce every kept quantised bit."""
+is bit-exact.  The decode of the GPU-encoded layer must also reproduce every kept quantised bit.
+The same for xorenc_encode_exhaustive against the oracle's 2^n_in search (Section 5.2): the minimum
+is unique and ties go to the smallest input on both sides."""
 import numpy as np
 import pytest
 
@@ -17,7 +19,13 @@ WIDE = [("lstm", 130, 3000, 192, 24), ("large_q1", 320, 1024, 128, 8), ("large_q
         ("fig1", 200, 448, 256, 32), ("tiny", 33, 70, 128, 16)]
 
 
-def gpu_encode(wl):
+# (config, m, n, n_out, n_in, S): 2^n_in inputs per slice on the oracle's side bounds the sizes
+EXHAUSTIVE = [("large_q1", 320, 1024, 64, 8, None), ("large_q1", 320, 1024, 64, 8, 0.75),
+              ("large_q2", 64, 4096, 64, 16, None), ("lstm", 66, 3000, 192, 16, None),
+              ("fig1", 200, 448, 256, 16, None), ("tiny", 33, 70, 128, 8, None), ("fc6", 97, 640, 64, 16, 0.8)]
+
+
+def gpu_encode(wl, exhaustive=False):
     import torch
     import paper_1905_10138_amd as xe
     dev = torch.device("cuda:0")
@@ -27,12 +35,13 @@ def gpu_encode(wl):
         np.stack([xe.pack_bits(wl.planes[p][:, :wl.n], n_out) for p in range(wl.cfg.q)]).view(np.int64)).to(dev)
     alpha = torch.from_numpy(wl.alpha).to(dev)
     M_rows = (wl.M.astype(np.uint64) << np.arange(wl.cfg.n_in, dtype=np.uint64)).sum(axis=1).astype(np.uint32)
-    return xe.encode(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha, n_out=n_out)
+    fn = xe.encode_exhaustive if exhaustive else xe.encode
+    return fn(wl.m, wl.n, wl.cfg.n_in, wl.cfg.q, M_rows, mask, planes, alpha, n_out=n_out)
 
 
-def _check_against_oracle(wl, enc):
+def _check_against_oracle(wl, enc, exhaustive=False):
     import paper_1905_10138_amd as xe
-    L = gpu_encode(wl)
+    L = gpu_encode(wl, exhaustive)
     host = L.to_host()
     assert xe.check_packed(host) == 0
     w_c, keep, n_patch, d_patch = xe.unpack(host)
@@ -50,6 +59,23 @@ def _check_against_oracle(wl, enc):
 def test_gpu_encoder_wide_slices(name, m, n, n_out, n_in):
     wl, enc = encoded_workload(name, m, n, n_out=n_out, n_in=n_in)
     _check_against_oracle(wl, enc)
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,S", EXHAUSTIVE)
+def test_gpu_exhaustive_encoder_matches_oracle(name, m, n, n_out, n_in, S):
+    wl, enc = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in, exhaustive=True)
+    _check_against_oracle(wl, enc, exhaustive=True)
+    _, alg1 = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in)
+    assert np.all(enc.n_patch <= alg1.n_patch)          # never worse than Algorithm 1, slice by slice
+
+
+def test_exhaustive_encoder_rejects_large_n_in():
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, _ = encoded_workload("tiny", 33, 70, n_out=128, n_in=24)
+    with pytest.raises(xe.XorencError):
+        gpu_encode(wl, exhaustive=True)
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("name,m,n", CASES)
