@@ -41,7 +41,7 @@ extern "C" {
 enum {
   XORENC_OK = 0,
   XORENC_EINVAL = -1,       /* null pointer, negative or inconsistent size */
-  XORENC_EUNSUPPORTED = -2, /* n_out not in {64,128,192,256}, n_in not in {8,16,24,32}, q not in 1..4, unknown dtype */
+  XORENC_EUNSUPPORTED = -2, /* n_out not in {64,128,192,256}, n_in not in 4..32, q not in 1..4, unknown dtype */
   XORENC_EALIGN = -3,       /* a device pointer or leading dimension breaks the stated alignment */
   XORENC_EHIP = -4,         /* a HIP runtime call failed; see xorenc_last_hip_error() */
   XORENC_EFORMAT = -5       /* xorenc_pack / xorenc_check_packed found malformed content */
@@ -56,6 +56,8 @@ enum { XORENC_X_F32 = 0, XORENC_X_BF16 = 1 };
 #define XORENC_ROWS_PER_UNIT 32
 #define XORENC_WORD_BITS 64
 #define XORENC_MAX_N_OUT 256
+#define XORENC_MIN_N_IN 4
+#define XORENC_MAX_N_IN 32
 
 /*
  * One encrypted weight matrix in the packed device layout.
@@ -72,8 +74,11 @@ enum { XORENC_X_F32 = 0, XORENC_X_BF16 = 1 };
  *
  *   mask      DEV  uint64[n_slots], 8-byte aligned.  Bit j of mask[slot(r,s)] = 1 iff weight
  *                  (r, 64 s + j) is kept (care); padding rows/columns are 0.
- *   enc       DEV  uint8[q][n_eslots][n_in/8]: the n_in encrypted bits of each slice of each
- *                  plane, little endian (bit j of the integer = x_j).  4-byte aligned.
+ *   enc       DEV  bit stream of q*n_eslots fields of n_in bits, 4-byte aligned: field
+ *                  p*n_eslots + eslot holds the encrypted bits of that slice of plane p (bit j of the
+ *                  field = x_j) and starts at bit (p*n_eslots + eslot)*n_in of the stream; bit k of the
+ *                  stream is bit k%32 of its k/32-th little-endian uint32.  The 32 slices of a unit thus
+ *                  fill exactly n_in dwords; for n_in a multiple of 8 this is uint8[q][n_eslots][n_in/8].
  *   patch_off DEV  uint32[q*n_units + 1], 4-byte aligned, non-decreasing;
  *                  entries [patch_off[p*n_units+u], patch_off[p*n_units+u+1]) belong to unit u
  *                  of plane p.
@@ -90,7 +95,7 @@ typedef struct xorenc_layer {
   uint32_t struct_size; /* = sizeof(xorenc_layer), ABI guard */
   int32_t m, n;
   int32_t n_out; /* 64, 128, 192 or 256 */
-  int32_t n_in;  /* 8, 16, 24 or 32 */
+  int32_t n_in;  /* XORENC_MIN_N_IN .. XORENC_MAX_N_IN */
   int32_t q;     /* 1..4 bit-planes */
   const uint32_t *M_rows;
   const uint8_t *enc;
@@ -103,7 +108,7 @@ typedef struct xorenc_layer {
 /* Element counts of the packed buffers for a shape (HOST arithmetic only). */
 typedef struct xorenc_sizes {
   int64_t n_pad, m_pad, spr, n_slots, n_units;
-  int64_t enc_bytes;       /* q*n_eslots*n_in/8 */
+  int64_t enc_bytes;       /* q*n_eslots*n_in/8 (n_eslots is a multiple of 32) */
   int64_t mask_words;      /* n_slots */
   int64_t patch_off_words; /* q*n_units + 1 */
   int64_t espr, n_eslots;  /* slices per row, m_pad*espr */
@@ -162,7 +167,7 @@ XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, int32_t n_out, const u
  *   M_rows     HOST uint32[n_out]
  *   mask       DEV  uint64[n_slots]      care mask, unit-major (the layer's mask buffer itself)
  *   planes     DEV  uint64[q][n_slots]   quantised bits, unit-major; bits at pruned positions are ignored
- *   enc_out    DEV  uint8[q][n_eslots][n_in/8]
+ *   enc_out    DEV  uint8[enc_bytes], 4-byte aligned: the bit stream described at xorenc_layer
  *   patch_off_out DEV uint32[q*n_units + 1]
  *   patch_out  DEV  uint16[patch_capacity]; entries beyond the capacity are not written.  The caller
  *              must compare patch_off_out[q*n_units] (the true total) with patch_capacity after the

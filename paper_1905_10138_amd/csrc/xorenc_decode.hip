@@ -25,7 +25,7 @@ int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   if (rc != XORENC_OK) return rc;
   if (!layer->M_rows || !layer->enc || !layer->mask || !layer->patch_off || !layer->alpha) return XORENC_EINVAL;
   if (sz.n_slots > (int64_t)1 << 31) return XORENC_EUNSUPPORTED;
-  const int nib = layer->n_in / 8;
+  const int nib = (layer->n_in + 7) / 8;
   if (((uintptr_t)layer->mask & 7) || ((uintptr_t)layer->patch_off & 3) || ((uintptr_t)layer->alpha & 3) ||
       ((uintptr_t)layer->patch & 1) || ((uintptr_t)layer->enc & 3))
     return XORENC_EALIGN;
@@ -42,6 +42,7 @@ int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   D->nrb = (int32_t)(sz.m_pad / 32);
   D->n_units = (int32_t)sz.n_units;
   D->nib = nib;
+  D->n_in = layer->n_in;
   D->q = layer->q;
   D->n_slots = sz.n_slots;
   D->n_eslots = sz.n_eslots;
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
       // word s of the row belongs to slice s / J and is word s % J of it
       const int64_t eslot = ((int64_t)rb * L.espr + s / L.J) * 32 + rr;
       const int wsel = s % L.J;
-      const uint32_t x = load_enc(L.enc + ((int64_t)p * L.n_eslots + eslot) * L.nib, L.nib);
+      const uint32_t x = load_enc(L.enc, (int64_t)p * L.n_eslots + eslot, L.n_in);
       uint32_t lo = 0, hi = 0;
       for (int b = 0; b < L.nib; ++b) {
         const int e = ((wsel * L.nib + b) << 8) + ((x >> (8 * b)) & 255);

@@ -16,7 +16,8 @@ struct DevLayer {
   const uint32_t *patch_off;
   const uint16_t *patch;
   const float *alpha;
-  int32_t m, n, spr, nrb, n_units, nib, q;
+  int32_t m, n, spr, nrb, n_units, nib, q;  // nib = ceil(n_in/8): byte-indexed XOR tables per word
+  int32_t n_in;
   int32_t J, espr;  // 64-bit words per slice (n_out/64), slices per row
   int64_t n_slots, n_eslots;
   // column j of M restricted to word w of a slice (rows 64 w .. 64 w + 63): lower and upper 32 rows
@@ -43,12 +44,35 @@ static __device__ inline void build_xor_tables(uint32_t *lut, const DevLayer &L)
   }
 }
 
-static __device__ inline uint32_t load_enc(const uint8_t *p, int nib) {
-  switch (nib) {
-    case 1: return p[0];
-    case 2: return *reinterpret_cast<const uint16_t *>(p);
-    case 3: return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16);
-    default: return *reinterpret_cast<const uint32_t *>(p);
+// field `e` (n_in bits at bit e*n_in) of the encrypted bit stream, seen as aligned dwords
+static __device__ inline uint32_t load_enc(const uint8_t *enc, int64_t e, int n_in) {
+  const uint32_t *d = reinterpret_cast<const uint32_t *>(enc);
+  const int64_t bit = e * n_in;
+  const int64_t i = bit >> 5;
+  const int sh = (int)(bit & 31);
+  uint32_t x = d[i] >> sh;
+  if (sh + n_in > 32) x |= d[i + 1] << (32 - sh);
+  return n_in < 32 ? (x & ((1u << n_in) - 1u)) : x;
+}
+
+// Lanes 32k .. 32k+31 hold the fields of the 32 slices of one unit (x, n_in bits each, field index
+// e0 + lane%32 with e0 a multiple of 32): write the unit's n_in dwords of the stream.  Every lane
+// of the wave must call this; lanes whose `valid` is false write nothing.
+static __device__ inline void store_enc_unit(uint8_t *enc, int64_t e, int n_in, uint32_t x, bool valid) {
+  const int rr = (int)(threadIdx.x & 31);
+  const int lo_bit = 32 * rr;             // this lane composes dword rr of the run (if rr < n_in)
+  const int first = lo_bit / n_in;        // first field that reaches into it
+  uint32_t word = 0;
+  const int span = 32 / n_in + 2;         // fields that can overlap one dword
+  for (int t = 0; t < span; ++t) {        // uniform
+    const int k = first + t;
+    const uint32_t xk = (uint32_t)__shfl((int)x, k & 31, 32);
+    const int pos = k * n_in - lo_bit;    // where field k starts relative to this dword
+    if (k < 32 && pos < 32) word |= pos >= 0 ? (xk << pos) : (xk >> (-pos));
+  }
+  if (valid && rr < n_in) {
+    uint32_t *d = reinterpret_cast<uint32_t *>(enc);
+    d[((e - rr) >> 5) * n_in + rr] = word;
   }
 }
 

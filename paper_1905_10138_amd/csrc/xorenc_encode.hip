@@ -16,7 +16,7 @@
 // the mismatches on its own slice.  Ties go to the smallest input read as an integer.
 #include <hip/hip_runtime.h>
 
-#include "xorenc_internal.h"
+#include "xorenc_device.h"
 
 namespace {
 
@@ -29,7 +29,7 @@ struct EncParams {
   uint64_t *pbits;      // [q][n_slots] patch bitmaps (workspace)
   uint32_t *counts;     // [q*n_units] patches per unit (workspace)
   int64_t n_slots, n_eslots;
-  int32_t n_units, n_in, nib, q, J, spr, espr;
+  int32_t n_units, n_in, q, J, spr, espr;
   uint32_t M_rows[XORENC_MAX_N_OUT];
 };
 
@@ -92,10 +92,7 @@ __global__ __launch_bounds__(ENC_THREADS) void encode_slices_kernel(EncParams P)
     const uint32_t v = ((rhsbits >> j) & 1u) ^ (__builtin_popcount(others) & 1u);
     x |= v << j;
   }
-  if (valid) {
-    uint8_t *dst = P.enc + ((int64_t)p * P.n_eslots + eslot) * P.nib;
-    for (int b = 0; b < P.nib; ++b) dst[b] = (uint8_t)(x >> (8 * b));
-  }
+  store_enc_unit(P.enc, (int64_t)p * P.n_eslots + eslot, P.n_in, x, valid);
 }
 
 struct ExhParams {
@@ -105,7 +102,7 @@ struct ExhParams {
   uint64_t *pbits;
   uint32_t *counts;
   int64_t n_slots, n_eslots;
-  int32_t n_units, n_in, nib, q, spr, espr;
+  int32_t n_units, n_in, q, spr, espr;
   uint64_t Mcol[XORENC_MAX_J][XORENC_EXH_MAX_N_IN];  // [w][j]: bit i = M[64 w + i][j]
 };
 
@@ -185,10 +182,7 @@ __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParam
     for (int o = 16; o >= 1; o >>= 1) cnt += __shfl_down(cnt, o, 32);
     if (valid && rr == 0) P.counts[(int64_t)p * P.n_units + unit0 + w] = (uint32_t)cnt;
   }
-  if (valid) {
-    uint8_t *dst = P.enc + ((int64_t)p * P.n_eslots + eslot) * P.nib;
-    for (int b = 0; b < P.nib; ++b) dst[b] = (uint8_t)(xb >> (8 * b));
-  }
+  store_enc_unit(P.enc, (int64_t)p * P.n_eslots + eslot, P.n_in, xb, valid);
 }
 
 // exclusive scan of counts[0..n) into off[0..n], one workgroup
@@ -260,7 +254,7 @@ int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32
   if (workspace_bytes < total * 8 + n_counts * 4) return XORENC_EINVAL;
   if (n_counts > (int64_t)1 << 30) return XORENC_EUNSUPPORTED;
   if (((uintptr_t)mask & 7) || ((uintptr_t)planes & 7) || ((uintptr_t)workspace & 7) ||
-      ((uintptr_t)patch_off_out & 3) || ((uintptr_t)patch_out & 1))
+      ((uintptr_t)patch_off_out & 3) || ((uintptr_t)patch_out & 1) || ((uintptr_t)enc_out & 3))
     return XORENC_EALIGN;
   for (int i = 0; i < n_out; ++i)
     if (n_in < 32 && (M_rows[i] >> n_in)) return XORENC_EINVAL;
@@ -282,7 +276,6 @@ int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32
     P.n_eslots = sz.n_eslots;
     P.n_units = (int32_t)sz.n_units;
     P.n_in = n_in;
-    P.nib = n_in / 8;
     P.q = q;
     P.spr = (int32_t)sz.spr;
     P.espr = (int32_t)sz.espr;
@@ -310,7 +303,6 @@ int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32
     P.n_eslots = sz.n_eslots;
     P.n_units = (int32_t)sz.n_units;
     P.n_in = n_in;
-    P.nib = n_in / 8;
     P.q = q;
     P.J = J;
     P.spr = (int32_t)sz.spr;

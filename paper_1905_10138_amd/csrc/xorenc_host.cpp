@@ -14,7 +14,7 @@ const char *xorenc_strerror(int32_t code) {
   switch (code) {
     case XORENC_OK: return "ok";
     case XORENC_EINVAL: return "invalid argument (null pointer, negative or inconsistent size)";
-    case XORENC_EUNSUPPORTED: return "unsupported configuration (n_out in {64,128,192,256}, n_in in {8,16,24,32}, q in 1..4)";
+    case XORENC_EUNSUPPORTED: return "unsupported configuration (n_out in {64,128,192,256}, n_in in 4..32, q in 1..4)";
     case XORENC_EALIGN: return "misaligned pointer or leading dimension";
     case XORENC_EHIP: return "HIP runtime call failed";
     case XORENC_EFORMAT: return "malformed compressed data";
@@ -24,7 +24,7 @@ const char *xorenc_strerror(int32_t code) {
 
 int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, xorenc_sizes *out) {
   if (!out || m <= 0 || n <= 0) return XORENC_EINVAL;
-  if (!(n_in == 8 || n_in == 16 || n_in == 24 || n_in == 32) || q < 1 || q > XORENC_MAX_Q) return XORENC_EUNSUPPORTED;
+  if (n_in < XORENC_MIN_N_IN || n_in > XORENC_MAX_N_IN || q < 1 || q > XORENC_MAX_Q) return XORENC_EUNSUPPORTED;
   if (n_out < 64 || n_out > XORENC_MAX_N_OUT || n_out % 64) return XORENC_EUNSUPPORTED;
   const int64_t espr = ((int64_t)n + n_out - 1) / n_out;
   const int64_t spr = espr * (n_out / 64);
@@ -36,11 +36,29 @@ int32_t xorenc_get_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t 
   out->n_slots = nrb * 32 * spr;
   out->n_eslots = nrb * 32 * espr;
   out->n_units = nrb * spr;
-  out->enc_bytes = (int64_t)q * out->n_eslots * (n_in / 8);
+  out->enc_bytes = (int64_t)q * (out->n_eslots / 32) * n_in * 4;  // n_in dwords per 32 slices
   out->mask_words = out->n_slots;
   out->patch_off_words = (int64_t)q * out->n_units + 1;
   return XORENC_OK;
 }
+
+namespace {
+
+// the n_in bits of slice e (all planes counted) sit at bit e*n_in of the stream, little-endian
+inline void put_enc_bits(uint8_t *enc, int64_t e, int n_in, uint32_t x) {
+  const int64_t bit = e * n_in;
+  for (int j = 0; j < n_in; ++j)
+    if ((x >> j) & 1u) enc[(bit + j) >> 3] |= (uint8_t)(1u << ((bit + j) & 7));
+}
+
+inline uint32_t get_enc_bits(const uint8_t *enc, int64_t e, int n_in) {
+  const int64_t bit = e * n_in;
+  uint32_t x = 0;
+  for (int j = 0; j < n_in; ++j) x |= (uint32_t)((enc[(bit + j) >> 3] >> ((bit + j) & 7)) & 1u) << j;
+  return x;
+}
+
+}  // namespace
 
 int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *w_c,
                     const uint64_t *keep, const uint16_t *n_patch, const uint8_t *d_patch, int64_t n_d_patch,
@@ -52,7 +70,6 @@ int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out
   if (n_d_patch > 0 && (!d_patch || !patch_out)) return XORENC_EINVAL;
   const int64_t spr = sz.spr, espr = sz.espr, l = (int64_t)m * espr;
   const int J = n_out / 64;
-  const int nib = n_in / 8;
   std::memset(enc_out, 0, (size_t)sz.enc_bytes);
   std::memset(mask_out, 0, (size_t)sz.mask_words * sizeof(uint64_t));
 
@@ -90,7 +107,7 @@ int32_t xorenc_pack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out
           const uint32_t x = w_c[(int64_t)p * l + t];
           if (n_in < 32 && (x >> n_in)) return XORENC_EFORMAT;
           const int64_t eslot = (rb * espr + S) * 32 + rr;
-          for (int b = 0; b < nib; ++b) enc_out[((int64_t)p * sz.n_eslots + eslot) * nib + b] = (uint8_t)(x >> (8 * b));
+          put_enc_bits(enc_out, (int64_t)p * sz.n_eslots + eslot, n_in, x);
         }
         const int64_t a = start[(int64_t)p * l + t], e = start[(int64_t)p * l + t + 1];
         for (int64_t i = a; i < e; ++i) {
@@ -113,7 +130,6 @@ int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_o
   if (!enc || !mask || !patch_off || !w_c_out || !keep_out || !n_patch_out) return XORENC_EINVAL;
   const int64_t spr = sz.spr, espr = sz.espr, l = (int64_t)m * espr;
   const int J = n_out / 64;
-  const int nib = n_in / 8;
   const int64_t total = patch_off[(int64_t)q * sz.n_units];
   if (total > 0 && (!patch || !d_patch_out)) return XORENC_EINVAL;
   // pass 1: per-slice counts and the other streams
@@ -128,9 +144,7 @@ int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_o
         if (p == 0) keep_out[r * spr + s] = mask[slot];
         if (s % J == 0) {
           const int64_t eslot = (rb * espr + S) * 32 + rr;
-          uint32_t x = 0;
-          for (int b = 0; b < nib; ++b) x |= (uint32_t)enc[((int64_t)p * sz.n_eslots + eslot) * nib + b] << (8 * b);
-          w_c_out[(int64_t)p * l + r * espr + S] = x;
+          w_c_out[(int64_t)p * l + r * espr + S] = get_enc_bits(enc, (int64_t)p * sz.n_eslots + eslot, n_in);
         }
       }
       const uint32_t a = patch_off[(int64_t)p * sz.n_units + u], e = patch_off[(int64_t)p * sz.n_units + u + 1];

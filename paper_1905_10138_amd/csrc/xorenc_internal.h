@@ -5,7 +5,6 @@
 #include "../../include/xorenc.h"
 
 #define XORENC_MAX_Q 4
-#define XORENC_MAX_N_IN 32
 #define XORENC_MAX_J (XORENC_MAX_N_OUT / 64) /* 64-bit words per slice */
 
 /* hipGetLastError() -> XORENC_OK / XORENC_EHIP; remembers the hipError_t per thread. */

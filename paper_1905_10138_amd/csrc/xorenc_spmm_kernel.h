@@ -73,7 +73,8 @@ struct BoolC {
   static constexpr bool value = V;
 };
 
-// NIBT = n_in/8 known at compile time (1..4), or 0: read it from the layer at run time.
+// NIBT = ceil(n_in/8), the number of byte-indexed tables, known at compile time (1..4; a field may
+// then straddle two dwords only for NIBT == 3), or 0: any n_in, read from the layer at run time.
 // JT = most 64-bit words per slice the variant has table space for: 1 (n_out = 64) or 4 (n_out up to 256).
 // PD = slice buffers per wave on the direct path: 2 (loads a slice and a half ahead, two waves per
 // SIMD hide each other's waits) or 1 (loads one slice ahead, more waves per SIMD do the hiding).
@@ -126,12 +127,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const uint32_t *const l_patch_off = L.patch_off;
   const uint16_t *const l_patch = L.patch;
   const float *const l_alpha = L.alpha;
-  const int l_m = L.m, l_n = L.n, l_spr = L.spr, l_nrb = L.nrb, l_n_units = L.n_units, l_nib = L.nib, l_q = L.q;
+  const int l_m = L.m, l_n = L.n, l_spr = L.spr, l_nrb = L.nrb, l_n_units = L.n_units, l_nib = L.nib, l_q = L.q,
+            l_n_in = L.n_in;
   const int64_t l_n_slots = L.n_slots;
   const int l_J = (JT > 1) ? L.J : 1, l_espr = (JT > 1) ? L.espr : L.spr;
   const int64_t l_n_eslots = (JT > 1) ? L.n_eslots : L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
-               "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_nib), "s"(l_q), "s"(l_n_slots), "s"(Xv), "s"(ldx), "s"(B),
+               "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_nib), "s"(l_n_in), "s"(l_q), "s"(l_n_slots), "s"(Xv), "s"(ldx), "s"(B),
                "s"(Y), "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
   // a wave that has not sent its first loads yet goes before the waves that already have
   __builtin_amdgcn_s_setprio(3);
@@ -142,6 +144,9 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const int row0 = blockIdx.x * ROWS;
   const int col0 = blockIdx.y * NR;  // first real X column of this workgroup
   const int nib = NIBT ? NIBT : l_nib;
+  const int n_in = l_n_in;
+  const uint32_t enc_bytes = (uint32_t)((l_n_eslots >> 3) * l_q * n_in);  // n_eslots is a multiple of 32
+  const uint32_t last_mask = (1u << (n_in - 8 * (nib - 1))) - 1u;         // index bits of the last table
   uint8_t *xbuf = xbuf_all + wave * XBUF;
 
   // ---- this wave's contiguous slice range [w0, w1) inside the workgroup's [s_begin, s_end)
@@ -161,7 +166,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint32_t *>(l_mask32), 0, (uint32_t)(l_n_slots * 8), kRsrcFlags);
   const __amdgpu_buffer_rsrc_t ersrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t *>(l_enc), 0, (uint32_t)(l_n_eslots * l_q * nib), kRsrcFlags);
+      const_cast<uint8_t *>(l_enc), 0, enc_bytes, kRsrcFlags);
 
   // ---- X loader.  One slice = 64 rows of X.  Chunk = 16 bytes of a row (8 bf16 / 4 fp32 columns).
   // XFAST: chunk i of a lane is (row i*RPI + lane/NCH, chunk lane%NCH), 16-byte loads.
@@ -271,17 +276,18 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   };
 
   // ---- compressed words of one slice for this lane: mask half and the dword(s) holding its
-  // encrypted bits (the n_in bits of slot rl start at byte rl*nib of the unit's run)
+  // encrypted bits (the n_in bits of slot rl start at bit rl*n_in of the unit's run of n_in dwords)
   struct Comp {
     uint32_t mw[RB];
     uint32_t e0[RB][Q];
     uint32_t e1[RB][Q];  // second dword, only needed when a 3-byte field straddles two dwords
   };
-  const bool two_dw = NIBT ? (NIBT == 3) : (nib == 3);
+  const bool two_dw = NIBT ? (NIBT == 3) : ((n_in & (n_in - 1)) != 0);
   const uint32_t m_lane_off = (uint32_t)(rl * 8 + g * 4);
-  const uint32_t e_byte = (uint32_t)(rl * nib);
-  const uint32_t e_lane_off = e_byte & ~3u;
-  const uint32_t e_shift = 8u * (e_byte & 3u);
+  const uint32_t e_bit = (uint32_t)(rl * n_in);
+  const uint32_t e_lane_off = (e_bit >> 5) << 2;
+  const uint32_t e_shift = e_bit & 31u;
+  const uint32_t e_plane_units = (uint32_t)(l_n_eslots >> 5), e_unit_bytes = (uint32_t)(n_in * 4);
   auto load_comp = [&](int s, Comp &c) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -295,7 +301,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
         c.mw[rb] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_lane_off, u * 256u, 0);
 #pragma unroll
         for (int p = 0; p < Q; ++p) {
-          const uint32_t so = ((uint32_t)p * (uint32_t)l_n_eslots + eu * 32u) * (uint32_t)nib;
+          const uint32_t so = ((uint32_t)p * e_plane_units + eu) * e_unit_bytes;
           c.e0[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so, 0);
           if (two_dw) c.e1[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so + 4u, 0);
         }
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
                        kRsrcFlags};
   const u32x4 edesc = {(uint32_t)reinterpret_cast<uint64_t>(l_enc),
                        (uint32_t)(reinterpret_cast<uint64_t>(l_enc) >> 32) & 0xffffu,
-                       (uint32_t)(l_n_eslots * l_q * nib), kRsrcFlags};
+                       enc_bytes, kRsrcFlags};
   constexpr int NGRP = NCH + KC;  // loads per slice
   uint32_t *const cbuf = reinterpret_cast<uint32_t *>(xbuf + (XDIR ? PD * XSL : 0));  // after the X slices
   const uint32_t cbuf_lds = __builtin_amdgcn_readfirstlane(
@@ -334,7 +340,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
       dma_dword(cbuf_lds + (k++) * 256, m_lane_off, mdesc, u * 256u);
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
-        const uint32_t so = ((uint32_t)p * (uint32_t)l_n_eslots + eu * 32u) * (uint32_t)nib;
+        const uint32_t so = ((uint32_t)p * e_plane_units + eu) * e_unit_bytes;
         dma_dword(cbuf_lds + (k++) * 256, e_lane_off, edesc, so);
         if (two_dw) dma_dword(cbuf_lds + (k++) * 256, e_lane_off, edesc, so + 4u);
       }
@@ -500,19 +506,20 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
           x = c.e0[rb][p] >> e_shift;
         uint32_t v;
         if constexpr (NIBT == 1) {
-          v = lut_g[2 * (x & 255)];
+          v = lut_g[2 * (x & last_mask)];
         } else if constexpr (NIBT == 2) {
-          const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
+          const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & last_mask))];
           v = t0 ^ t1;
         } else if constexpr (NIBT == 3) {
           const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
-          const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))];
+          const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & last_mask))];
           v = t0 ^ t1 ^ t2;
         } else if constexpr (NIBT == 4) {
           const uint32_t t0 = lut_g[2 * (x & 255)], t1 = lut_g[2 * (256 + ((x >> 8) & 255))];
-          const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))], t3 = lut_g[2 * (768 + (x >> 24))];
+          const uint32_t t2 = lut_g[2 * (512 + ((x >> 16) & 255))], t3 = lut_g[2 * (768 + ((x >> 24) & last_mask))];
           v = t0 ^ t1 ^ t2 ^ t3;
         } else {
+          if (n_in < 32) x &= (1u << n_in) - 1u;
           v = lut_g[2 * (x & 255)];
           if (nib > 1) v ^= lut_g[2 * (256 + ((x >> 8) & 255))];  // uniform branches
           if (nib > 2) v ^= lut_g[2 * (512 + ((x >> 16) & 255))];

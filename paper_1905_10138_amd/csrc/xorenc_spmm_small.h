@@ -43,10 +43,11 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
   const uint32_t *const l_patch_off = L.patch_off;
   const uint16_t *const l_patch = L.patch;
   const float *const l_alpha = L.alpha;
-  const int l_m = L.m, l_n = L.n, l_spr = L.spr, l_nrb = L.nrb, l_n_units = L.n_units, l_q = L.q;
+  const int l_m = L.m, l_n = L.n, l_spr = L.spr, l_nrb = L.nrb, l_n_units = L.n_units, l_q = L.q,
+            n_in = L.n_in;
   const int64_t l_n_slots = L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
-               "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_q), "s"(l_n_slots), "s"(X), "s"(ldx), "s"(B), "s"(Y),
+               "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_q), "s"(n_in), "s"(l_n_slots), "s"(X), "s"(ldx), "s"(B), "s"(Y),
                "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -76,11 +77,13 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
   const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint32_t *>(l_mask32), 0, (uint32_t)(l_n_slots * 8), kRsrcFlags);
   const __amdgpu_buffer_rsrc_t ersrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t *>(l_enc), 0, (uint32_t)(l_n_slots * l_q * nib), kRsrcFlags);
+      const_cast<uint8_t *>(l_enc), 0, (uint32_t)((l_n_slots >> 3) * l_q * n_in), kRsrcFlags);
   const uint32_t m_lane_off = (uint32_t)(rl * 8 + g * 4);
-  const uint32_t e_byte = (uint32_t)(rl * nib);
-  const uint32_t e_lane_off = e_byte & ~3u;
-  const uint32_t e_shift = 8u * (e_byte & 3u);
+  const uint32_t e_bit = (uint32_t)(rl * n_in);  // the n_in bits of slot rl start at bit rl*n_in of the unit's run
+  const uint32_t e_lane_off = (e_bit >> 5) << 2;
+  const uint32_t e_shift = e_bit & 31u;
+  const uint32_t e_plane_units = (uint32_t)(l_n_slots >> 5), e_unit_bytes = (uint32_t)(n_in * 4);
+  const uint32_t last_mask = (1u << (n_in - 8 * (nib - 1))) - 1u;  // index bits of the last table
   auto load_comp = [&](int s, Comp &c) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
         c.mw[rb] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_lane_off, u * 256u, 0);
 #pragma unroll
         for (int p = 0; p < Q; ++p) {
-          const uint32_t so = ((uint32_t)p * (uint32_t)l_n_slots + u * 32u) * (uint32_t)nib;
+          const uint32_t so = ((uint32_t)p * e_plane_units + u) * e_unit_bytes;
           c.e0[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so, 0);
           if (two_dw) c.e1[rb][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, e_lane_off, so + 4u, 0);
         }
@@ -216,10 +219,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
           x = __builtin_amdgcn_alignbit(c.e1[rb][p], c.e0[rb][p], e_shift);
         else
           x = c.e0[rb][p] >> e_shift;
-        uint32_t v = lut_g[2 * (x & 255)];
-        if constexpr (NIBT >= 2) v ^= lut_g[2 * (256 + ((x >> 8) & 255))];
-        if constexpr (NIBT >= 3) v ^= lut_g[2 * (512 + ((x >> 16) & 255))];
-        if constexpr (NIBT >= 4) v ^= lut_g[2 * (768 + (x >> 24))];
+        uint32_t v = lut_g[2 * (x & (NIBT == 1 ? last_mask : 255u))];
+        if constexpr (NIBT >= 2) v ^= lut_g[2 * (256 + ((x >> 8) & (NIBT == 2 ? last_mask : 255u)))];
+        if constexpr (NIBT >= 3) v ^= lut_g[2 * (512 + ((x >> 16) & (NIBT == 3 ? last_mask : 255u)))];
+        if constexpr (NIBT >= 4) v ^= lut_g[2 * (768 + ((x >> 24) & last_mask))];
         S[rb][p] = v;
       }
   };
@@ -401,6 +404,8 @@ template <int Q>
 bool dispatch_small_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
                       int x_fast, hipStream_t st, int32_t *rc) {
   if (x_dtype != XORENC_X_BF16 || x_fast || D.J != 1) return false;
+  // one dword of encrypted bits per lane and slice (two for 17..24 bits), as in the specialised main kernels
+  if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
   constexpr int RB = (Q <= 3) ? 2 : 1;
   constexpr int NW = (Q == 1) ? 16 : (Q == 2 ? 12 : 8);
   int ks = 1, sps = 0;

@@ -16,6 +16,10 @@ FULL = [("fig1", None, None), ("fc6", None, None), ("lstm", None, None), ("large
 # slices of two, three and four 64-bit words: (name, m, n, n_out, n_in)
 WIDE = [("lstm", 130, 3000, 192, 24), ("large_q1", 320, 1024, 128, 8), ("large_q2", 96, 4096, 256, 16),
         ("fig1", 200, 448, 256, 32), ("tiny", 33, 70, 128, 16)]
+# encrypted vectors that are not whole bytes (bit-packed stream): (name, m, n, n_out, n_in)
+ANY_N_IN = [("lstm", 130, 3000, 192, 20), ("tiny", 256, 256, 64, 13), ("fc6", 97, 640, 128, 27),
+            ("large_q1", 320, 1024, 64, 4), ("large_q2", 96, 4096, 128, 31), ("fig1", 200, 448, 64, 9),
+            ("lstm", 130, 3000, 64, 17)]
 
 
 def _gpu_layer(name, m, n, n_out=None, n_in=None):
@@ -49,7 +53,7 @@ def test_dense_f32_and_bf16_bit_exact(name, m, n):
     assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(want))
 
 
-@pytest.mark.parametrize("name,m,n,n_out,n_in", WIDE)
+@pytest.mark.parametrize("name,m,n,n_out,n_in", WIDE + ANY_N_IN)
 def test_wide_slices_planes_and_dense_bit_exact(name, m, n, n_out, n_in):
     import torch
     import paper_1905_10138_amd as xe

@@ -16,13 +16,17 @@ CASES = [("tiny", 256, 256), ("fig1", 200, 448), ("fc6", 97, 640), ("lstm", 130,
 
 
 WIDE = [("lstm", 130, 3000, 192, 24), ("large_q1", 320, 1024, 128, 8), ("large_q2", 96, 4096, 256, 16),
-        ("fig1", 200, 448, 256, 32), ("tiny", 33, 70, 128, 16)]
+        ("fig1", 200, 448, 256, 32), ("tiny", 33, 70, 128, 16),
+        # encrypted vectors that are not whole bytes
+        ("lstm", 130, 3000, 192, 20), ("tiny", 256, 256, 64, 13), ("fc6", 97, 640, 128, 27), ("large_q1", 320, 1024, 64, 4),
+        ("large_q2", 96, 4096, 128, 31), ("fig1", 200, 448, 64, 9), ("lstm", 130, 3000, 64, 17)]
 
 
 # (config, m, n, n_out, n_in, S): 2^n_in inputs per slice on the oracle's side bounds the sizes
 EXHAUSTIVE = [("large_q1", 320, 1024, 64, 8, None), ("large_q1", 320, 1024, 64, 8, 0.75),
               ("large_q2", 64, 4096, 64, 16, None), ("lstm", 66, 3000, 192, 16, None),
-              ("fig1", 200, 448, 256, 16, None), ("tiny", 33, 70, 128, 8, None), ("fc6", 97, 640, 64, 16, 0.8)]
+              ("fig1", 200, 448, 256, 16, None), ("tiny", 33, 70, 128, 8, None), ("fc6", 97, 640, 64, 16, 0.8),
+              ("fc6", 97, 640, 64, 12, 0.8), ("tiny", 33, 70, 128, 5, None), ("lstm", 66, 3000, 192, 15, None)]
 
 
 def gpu_encode(wl, exhaustive=False):

@@ -99,6 +99,26 @@ WIDE_CASES = [
 ]
 
 
+# n_in that is not a whole number of bytes: 20 and 17 (one or two dwords per lane, specialised kernels),
+# 4 (several slices per byte), and widths that take the general kernel (13, 27, 31, 9)
+ANY_N_IN_CASES = [
+    ("lstm", 130, 3000, 192, 20, 32, "bf16"), ("lstm", 130, 3000, 192, 20, 1, "bf16"), ("lstm", 130, 3000, 192, 20, 40, "f32"),
+    ("lstm", 130, 3000, 64, 17, 8, "bf16"), ("lstm", 130, 3000, 64, 17, 3, "bf16"), ("lstm", 130, 3000, 64, 20, 7, "bf16"),
+    ("large_q1", 320, 1024, 64, 4, 64, "bf16"), ("large_q1", 320, 1024, 64, 4, 5, "bf16"),
+    ("large_q1", 320, 1024, 64, 20, 256, "bf16"), ("large_q1", 320, 1024, 64, 20, 64, "bf16"),
+    ("tiny", 256, 256, 64, 13, 8, "f32"), ("tiny", 256, 256, 64, 13, 64, "bf16"), ("fc6", 97, 640, 128, 27, 64, "bf16"),
+    ("fc6", 97, 640, 128, 27, 1, "bf16"), ("large_q2", 96, 4096, 128, 31, 72, "bf16"), ("fig1", 200, 448, 64, 9, 6, "bf16"),
+    ("large_q2", 96, 4096, 64, 20, 64, "bf16"),
+]
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,B,dtype", ANY_N_IN_CASES)
+def test_spmm_with_bit_packed_encrypted_vectors(name, m, n, n_out, n_in, B, dtype):
+    got, want = _run(name, m, n, B, dtype, n_out=n_out, n_in=n_in)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("name,m,n,n_out,n_in,B,dtype", WIDE_CASES)
 def test_spmm_with_slices_of_several_words(name, m, n, n_out, n_in, B, dtype):
     """n_out = 128, 192, 256: one encrypted vector feeds two to four 64-bit words of a row."""
@@ -109,8 +129,10 @@ def test_spmm_with_slices_of_several_words(name, m, n, n_out, n_in, B, dtype):
 
 def test_paper_region_full_size():
     """The paper's best compression is near n_out = 200 with n_in = 20: the LSTM-shaped layer at
-    n_out = 192, n_in = 24, full size, fused product at B = 32."""
+    n_out = 192 with n_in = 24 and with n_in = 20, full size, fused product at B = 32."""
     got, want = _run("lstm", None, None, 32, "bf16", n_out=192, n_in=24)
+    assert rel_fro(got, want) <= TOL["bf16"]
+    got, want = _run("lstm", None, None, 32, "bf16", n_out=192, n_in=20)
     assert rel_fro(got, want) <= TOL["bf16"]
 
 

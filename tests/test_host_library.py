@@ -43,17 +43,21 @@ def test_sizes():
         with pytest.raises(xe.XorencError) as e:
             xe.get_sizes(*bad)
         assert e.value.code == -1
-    for bad in [(8, 8, 12, 1), (8, 8, 8, 5), (8, 8, 40, 1)]:
+    s = xe.get_sizes(6000, 3000, 20, 3, 192)                     # 20 encrypted bits: 20 dwords per 32 slices
+    assert s["enc_bytes"] == 3 * (s["n_eslots"] // 32) * 20 * 4
+    for bad in [(8, 8, 3, 1), (8, 8, 8, 5), (8, 8, 40, 1)]:
         with pytest.raises(xe.XorencError) as e:
             xe.get_sizes(*bad)
         assert e.value.code == -2
 
 
-@pytest.mark.parametrize("name,m,n,n_out", [("tiny", 70, 256, 64), ("lstm", 45, 200, 64), ("large_q2", 64, 512, 64),
-                                             ("fc6", 33, 130, 64), ("lstm", 45, 200, 192), ("large_q2", 64, 500, 128),
-                                             ("fig1", 40, 700, 256)])
-def test_pack_unpack_roundtrip(name, m, n, n_out):
-    wl, enc = encoded_workload(name, m, n, n_out=n_out)
+@pytest.mark.parametrize("name,m,n,n_out,n_in", [
+    ("tiny", 70, 256, 64, None), ("lstm", 45, 200, 64, None), ("large_q2", 64, 512, 64, None),
+    ("fc6", 33, 130, 64, None), ("lstm", 45, 200, 192, None), ("large_q2", 64, 500, 128, None),
+    ("fig1", 40, 700, 256, None), ("lstm", 45, 200, 192, 20), ("tiny", 70, 256, 64, 13), ("fc6", 33, 130, 128, 27),
+    ("large_q1", 64, 512, 64, 4), ("large_q2", 64, 500, 128, 31)])
+def test_pack_unpack_roundtrip(name, m, n, n_out, n_in):
+    wl, enc = encoded_workload(name, m, n, n_out=n_out, n_in=n_in)
     w_c, keep, n_patch, d_patch, M_rows = paper_format_arrays(enc)
     L = pack_encoded(enc)
     assert xe.check_packed(L) == 0
@@ -65,15 +69,15 @@ def test_pack_unpack_roundtrip(name, m, n, n_out):
     spr = wl.n_pad // 64
     espr = wl.n_pad // n_out
     n_eslots = L.mask.size // J
-    nib = enc.n_in // 8
+    stream = np.unpackbits(L.enc, bitorder="little")              # bit k of the stream
     rng = np.random.default_rng(0)
     for _ in range(50):
         r, s, p = rng.integers(m), rng.integers(spr), rng.integers(enc.q)
         slot = ((r // 32) * spr + s) * 32 + r % 32
         assert L.mask[slot] == keep[r * spr + s]
         eslot = ((r // 32) * espr + s // J) * 32 + r % 32
-        got = int.from_bytes(L.enc[(p * n_eslots + eslot) * nib:(p * n_eslots + eslot + 1) * nib].tobytes(), "little")
-        assert got == w_c[p, r * espr + s // J]
+        field = stream[(p * n_eslots + eslot) * enc.n_in:(p * n_eslots + eslot + 1) * enc.n_in]
+        assert int((field.astype(np.uint64) << np.arange(enc.n_in, dtype=np.uint64)).sum()) == w_c[p, r * espr + s // J]
     assert int(L.patch_off[-1]) == d_patch.size
     assert np.all(np.diff(L.patch_off.astype(np.int64)) >= 0)
 
