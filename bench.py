@@ -224,16 +224,17 @@ def fig1_extra(xe, torch, dev, args):
     return res
 
 
-def wide_extra(xe, torch, dev, args, base_cfg):
-    """The default workload re-encoded with slices of 192 bits and n_in = 24 (the region where the paper
-    reports its best ratios, Section 3.3): same bits per weight for the encrypted stream, fewer patches."""
+def wide_extra(xe, torch, dev, args, base_cfg, n_in=24):
+    """The default workload re-encoded with slices of 192 bits and n_in = 24 or 20 (the region where the
+    paper reports its best ratios, Section 3.3): same or fewer bits per weight for the encrypted stream,
+    fewer patches."""
     import dataclasses
 
     from synth_inputs import make_workload
-    cfg = dataclasses.replace(base_cfg, n_out=192, n_in=24)
+    cfg = dataclasses.replace(base_cfg, n_out=192, n_in=n_in)
     wl = make_workload(cfg)
     layer = build_layer(wl, xe, torch, dev)
-    res = {"workload": f"{cfg.name}: W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in=24 n_out=192 bf16",
+    res = {"workload": f"{cfg.name}: W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in={n_in} n_out=192 bf16",
            "compressed_bytes": layer.compressed_bytes(), "patches": int(layer.patch.numel())}
     for B in (8, 64):
         stored, _ = wl.X(B)
@@ -366,6 +367,7 @@ def main():
         extra["fig1"] = fig1_extra(xe, torch, dev, args)
     if not args.no_wide and cfg.n_out == 64:
         extra["n_out_192"] = wide_extra(xe, torch, dev, args, cfg)
+        extra["n_out_192_n_in_20"] = wide_extra(xe, torch, dev, args, cfg, n_in=20)
     if not args.no_encoder:
         extra["encoder"] = encoder_extra(xe, torch, dev, cfg)
     if args.copy_calibration:
