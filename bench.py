@@ -251,6 +251,22 @@ def wide_extra(xe, torch, dev, args, base_cfg, n_in=24):
     return res
 
 
+def storage_extra(xe, layer):
+    """Bits per weight of the quantised stream (everything but the mask and alpha): this library's packed
+    layout (enc + patch entries of 16 bits + one 32-bit offset per unit) next to the paper's format as a bit
+    stream (Section 3.2) with one n_patch width per plane and per block of 1024 and 32 slices (Section 5.2)."""
+    host = layer.to_host()
+    w_c, keep, n_patch, d_patch = xe.unpack(host)
+    weights = float(host.m) * host.n
+    res = {"packed_bits_per_weight": 8.0 * (host.enc.nbytes + host.patch.nbytes + host.patch_off.nbytes) / weights,
+           "mask_bits_per_weight": 8.0 * host.mask.nbytes / weights, "patches": int(d_patch.size)}
+    for name, blk in (("plane", n_patch.shape[1]), ("1024", 1024), ("32", 32)):
+        sz = xe.paper_sizes(host.m, host.n, host.n_in, host.q, n_patch, blk, host.n_out)
+        res[f"paper_bits_per_weight_block_{name}"] = (sz["total_bits"] - sz["header_bits"]) / weights
+        res[f"paper_header_bits_per_weight_block_{name}"] = sz["header_bits"] / weights
+    return res
+
+
 def encoder_extra(xe, torch, dev, base_cfg):
     """Both GPU encoders (Algorithm 1; the 2^n_in search of Section 5.2) on the default matrix, at its own
     slice geometry and at n_out = 128 / n_in = 16.  Times are host wall-clock around the binding call
@@ -368,6 +384,7 @@ def main():
     if not args.no_wide and cfg.n_out == 64:
         extra["n_out_192"] = wide_extra(xe, torch, dev, args, cfg)
         extra["n_out_192_n_in_20"] = wide_extra(xe, torch, dev, args, cfg, n_in=20)
+    extra["storage"] = storage_extra(xe, layer)
     if not args.no_encoder:
         extra["encoder"] = encoder_extra(xe, torch, dev, cfg)
     if args.copy_calibration:

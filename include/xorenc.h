@@ -145,6 +145,44 @@ XORENC_API int32_t xorenc_unpack(int32_t m, int32_t n, int32_t n_in, int32_t q, 
                                  uint32_t *w_c_out, uint64_t *keep_out, uint16_t *n_patch_out, uint8_t *d_patch_out);
 
 /*
+ * The compressed format of Section 3.2 as one bit stream, with the n_patch field width chosen per block
+ * of slices (blocked n_patch assignment, Section 5.2).  All pointers HOST; the arrays are those of
+ * xorenc_pack / xorenc_unpack (paper order).  Per plane, planes back to back without padding:
+ *   1. l = m*espr fields of n_in bits: w^c of each slice;
+ *   2. per block of block_slices consecutive slices (the last may be shorter): 8 bits = width w_b of the
+ *      block's n_patch fields, then one field of w_b bits per slice; w_b is the smallest width that holds
+ *      the block's largest n_patch;
+ *   3. sum(n_patch) fields of ceil(lg n_out) bits: the patch positions, slice by slice, ascending.
+ * Fields are little endian; bit k of the stream is bit k%8 of byte k/8.  The 8 bits per block are
+ * bookkeeping outside the paper's count (Eq. (2)) and are reported separately.
+ */
+typedef struct xorenc_paper_bits {
+  int64_t wc_bits;      /* q*l*n_in */
+  int64_t n_patch_bits; /* sum over blocks: slices of the block * w_b */
+  int64_t d_patch_bits; /* sum(n_patch) * ceil(lg n_out) */
+  int64_t header_bits;  /* 8 per block */
+  int64_t total_bits;
+} xorenc_paper_bits;
+
+/* Sizes of the stream's parts.  XORENC_EFORMAT if an n_patch exceeds n_out. */
+XORENC_API int32_t xorenc_paper_sizes(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                      const uint16_t *n_patch, int64_t block_slices, xorenc_paper_bits *out);
+
+/* Writes the stream into out[0 .. out_bytes) (zero-filled first).  XORENC_EINVAL if it does not fit,
+ * XORENC_EFORMAT if n_d_patch != sum(n_patch), a w^c has bits beyond n_in or a position is >= n_out. */
+XORENC_API int32_t xorenc_paper_export(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *w_c,
+                                       const uint16_t *n_patch, const uint8_t *d_patch, int64_t n_d_patch,
+                                       int64_t block_slices, uint8_t *out, int64_t out_bytes);
+
+/* Reads a stream back.  *n_d_patch_out receives sum(n_patch) even when it exceeds d_patch_capacity (then
+ * XORENC_EINVAL is returned and the caller retries with a larger d_patch_out).  XORENC_EFORMAT if the stream
+ * ends early or holds a width above 9, an n_patch above n_out or a position >= n_out. */
+XORENC_API int32_t xorenc_paper_import(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                       int64_t block_slices, const uint8_t *in, int64_t in_bytes, uint32_t *w_c_out,
+                                       uint16_t *n_patch_out, uint8_t *d_patch_out, int64_t d_patch_capacity,
+                                       int64_t *n_d_patch_out);
+
+/*
  * Content check of a packed layer whose buffers are all HOST copies: offsets non-decreasing,
  * entries sorted and unique within a unit, rows < 32, no patch on a padding row, mask zero on
  * padding rows and columns, M_rows within n_in bits.  XORENC_EFORMAT on the first violation.

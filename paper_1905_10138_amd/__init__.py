@@ -16,6 +16,9 @@ from .binding import (
     load_library,
     pack,
     pack_bits,
+    paper_export,
+    paper_import,
+    paper_sizes,
     spmm,
     strerror,
     unpack,
@@ -25,5 +28,5 @@ from .binding import (
 __all__ = [
     "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode", "encode", "encode_exhaustive",
     "pack_bits",
-    "get_sizes", "library_path", "load_library", "pack", "spmm", "strerror", "unpack", "version",
+    "paper_export", "paper_import", "paper_sizes", "get_sizes", "library_path", "load_library", "pack", "spmm", "strerror", "unpack", "version",
 ]

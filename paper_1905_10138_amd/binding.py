@@ -75,6 +75,12 @@ def load_library():
     lib.xorenc_pack_bits.argtypes = [i32, i32, i32, vp, i64, vp]
     lib.xorenc_encode.restype = i32
     lib.xorenc_encode.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    lib.xorenc_paper_sizes.restype = i32
+    lib.xorenc_paper_sizes.argtypes = [i32, i32, i32, i32, i32, vp, i64, vp]
+    lib.xorenc_paper_export.restype = i32
+    lib.xorenc_paper_export.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i64, i64, vp, i64]
+    lib.xorenc_paper_import.restype = i32
+    lib.xorenc_paper_import.argtypes = [i32, i32, i32, i32, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.xorenc_encode_exhaustive.restype = i32
     lib.xorenc_encode_exhaustive.argtypes = lib.xorenc_encode.argtypes
     lib.xorenc_decode.restype = i32
@@ -207,6 +213,51 @@ def unpack(layer: PackedLayer):
                              _np_ptr(w_c), _np_ptr(keep), _np_ptr(n_patch),
                              _np_ptr(d_patch) if d_patch.size else None), "xorenc_unpack")
     return w_c, keep, n_patch, d_patch
+
+
+class _PaperBits(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int64) for k in ("wc_bits", "n_patch_bits", "d_patch_bits", "header_bits", "total_bits")]
+
+
+def paper_sizes(m, n, n_in, q, n_patch, block_slices, n_out: int = 64) -> dict:
+    """xorenc_paper_sizes: bits of the parts of the paper-format stream (n_patch: uint16 [q, l])."""
+    n_patch = _as(n_patch, np.uint16)
+    out = _PaperBits()
+    _check(load_library().xorenc_paper_sizes(m, n, n_in, q, n_out, _np_ptr(n_patch), int(block_slices),
+                                             ctypes.byref(out)), "xorenc_paper_sizes")
+    return {k: int(getattr(out, k)) for k, _ in _PaperBits._fields_}
+
+
+def paper_export(m, n, n_in, q, w_c, n_patch, d_patch, block_slices, n_out: int = 64) -> np.ndarray:
+    """xorenc_paper_export: the arrays of `unpack` -> the bit stream (uint8 array)."""
+    w_c, n_patch, d_patch = _as(w_c, np.uint32), _as(n_patch, np.uint16), _as(d_patch, np.uint8)
+    nbytes = (paper_sizes(m, n, n_in, q, n_patch, block_slices, n_out)["total_bits"] + 7) // 8
+    out = np.empty(nbytes, np.uint8)
+    _check(load_library().xorenc_paper_export(m, n, n_in, q, n_out, _np_ptr(w_c), _np_ptr(n_patch),
+                                              _np_ptr(d_patch) if d_patch.size else None, d_patch.size,
+                                              int(block_slices), _np_ptr(out) if nbytes else None, nbytes),
+           "xorenc_paper_export")
+    return out
+
+
+def paper_import(m, n, n_in, q, stream, block_slices, n_out: int = 64):
+    """xorenc_paper_import: the bit stream -> (w_c uint32[q,l], n_patch uint16[q,l], d_patch uint8[])."""
+    stream = _as(stream, np.uint8)
+    l = m * get_sizes(m, n, n_in, q, n_out)["espr"]
+    w_c = np.empty((q, l), np.uint32)
+    n_patch = np.empty((q, l), np.uint16)
+    total = ctypes.c_int64(0)
+    cap = max(16, stream.size)
+    while True:
+        d_patch = np.empty(cap, np.uint8)
+        rc = load_library().xorenc_paper_import(m, n, n_in, q, n_out, int(block_slices), _np_ptr(stream), stream.size,
+                                                _np_ptr(w_c), _np_ptr(n_patch), _np_ptr(d_patch), cap,
+                                                ctypes.byref(total))
+        if rc == -1 and total.value > cap:
+            cap = int(total.value)
+            continue
+        _check(rc, "xorenc_paper_import")
+        return w_c, n_patch, d_patch[:total.value].copy()
 
 
 def pack_bits(a: np.ndarray, n_out: int = 64) -> np.ndarray:

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libxorenc.so")
-SOURCES = ["xorenc_host.cpp", "xorenc_decode.hip", "xorenc_encode.hip", "xorenc_spmm.hip",
+SOURCES = ["xorenc_host.cpp", "xorenc_paper.cpp", "xorenc_decode.hip", "xorenc_encode.hip", "xorenc_spmm.hip",
            "xorenc_spmm_q1.hip", "xorenc_spmm_q2.hip", "xorenc_spmm_q3.hip", "xorenc_spmm_q4.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics", "-fvisibility=hidden",

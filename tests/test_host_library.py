@@ -19,7 +19,8 @@ def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "xorenc.h")).read()
     names = set(re.findall(r"XORENC_API[^;(]*?\b(xorenc_\w+)\s*\(", text))
     assert {"xorenc_decode", "xorenc_spmm", "xorenc_pack", "xorenc_unpack", "xorenc_get_sizes",
-            "xorenc_encode", "xorenc_encode_exhaustive", "xorenc_check_packed", "xorenc_version", "xorenc_strerror",
+            "xorenc_encode", "xorenc_encode_exhaustive", "xorenc_paper_sizes", "xorenc_paper_export", "xorenc_paper_import",
+            "xorenc_check_packed", "xorenc_version", "xorenc_strerror",
             "xorenc_last_hip_error"} <= names
     for n in names:
         assert hasattr(lib, n), n
@@ -143,3 +144,30 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libxorenc.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.load_library()
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,S", [("large_q1", 64, 512, 64, 8, None), ("lstm", 45, 200, 192, 20, None),
+                                                  ("fc6", 33, 130, 128, 16, 0.7), ("tiny", 70, 256, 64, 13, None)])
+def test_paper_format_stream_matches_oracle(name, m, n, n_out, n_in, S):
+    """The library's bit stream of Section 3.2's format with blocked n_patch widths (Section 5.2) against the
+    oracle's writer, byte for byte, starting from the packed layer; and its reader against the arrays."""
+    from oracle import gf2, paper_format
+    wl, enc = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in)
+    L = pack_encoded(enc)
+    w_c, keep, n_patch, d_patch = xe.unpack(L)
+    for blk in (enc.l, 32, 7):
+        want_sizes = paper_format.sizes(enc.n_in, enc.n_out, enc.n_patch, blk)
+        got_sizes = xe.paper_sizes(enc.m, enc.n, enc.n_in, enc.q, n_patch, blk, enc.n_out)
+        assert got_sizes == {"wc_bits": want_sizes.wc_bits, "n_patch_bits": want_sizes.n_patch_bits,
+                             "d_patch_bits": want_sizes.d_patch_bits, "header_bits": want_sizes.header_bits,
+                             "total_bits": want_sizes.total_bits}
+        stream = xe.paper_export(enc.m, enc.n, enc.n_in, enc.q, w_c, n_patch, d_patch, blk, enc.n_out)
+        want = paper_format.write_stream(enc.n_in, enc.n_out, gf2.bits_to_int(enc.w_c), enc.n_patch, enc.d_patch, blk)
+        assert stream.tobytes() == want
+        w2, np2, dp2 = xe.paper_import(enc.m, enc.n, enc.n_in, enc.q, stream, blk, enc.n_out)
+        assert np.array_equal(w2, w_c) and np.array_equal(np2, n_patch) and np.array_equal(dp2, d_patch)
+    # damaged streams are rejected, not read out of bounds
+    with pytest.raises(xe.XorencError):
+        xe.paper_import(enc.m, enc.n, enc.n_in, enc.q, stream[:len(stream) // 2], 7, enc.n_out)
+    with pytest.raises(xe.XorencError):
+        xe.paper_sizes(enc.m, enc.n, enc.n_in, enc.q, n_patch, 0, enc.n_out)
