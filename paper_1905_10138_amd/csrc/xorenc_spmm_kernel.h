@@ -79,7 +79,7 @@ struct BoolC {
 // PD = slice buffers per wave on the direct path: 2 (loads a slice and a half ahead, two waves per
 // SIMD hide each other's waits) or 1 (loads one slice ahead, more waves per SIMD do the hiding).
 template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
-__global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
+__global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
                                                       int use_atomic) {
   constexpr int CW = 32 * NCB;                 // bf16 columns held in LDS per X row
@@ -103,7 +103,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_kernel(DevLayer L, const void *_
   constexpr int TILE = CW * TS;                // a tile is stored column-major: [column][row]
   // The epilogue keeps NREG reduction tiles in LDS (over the then idle X buffers): as many as fit
   // next to the tables, at most one per wave, and a divisor of NW so that the rounds are even.
-  constexpr int TILE_BUDGET = (JT == 1) ? 148 * 1024 : 160 * 1024 - 2048 - JT * NIBMAX * 2048;
+  // (four-wave workgroups are meant to run two per CU: half of the LDS each)
+  constexpr int TILE_BUDGET = (NW == 4 && XDIR && JT == 1) ? 80 * 1024 - 1024 - NW * NIBMAX * 2048
+                              : (JT == 1)                ? 148 * 1024
+                                                         : 160 * 1024 - 2048 - JT * NIBMAX * 2048;
   constexpr int FIT = TILE_BUDGET / (TILE * 4);
   constexpr int NREG = largest_divisor_at_most(NW, FIT < 8 ? FIT : 8);
   constexpr int LDSB = (NW * XBUF > NREG * TILE * 4) ? NW * XBUF : NREG * TILE * 4;
@@ -898,6 +901,10 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     }
     if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
+    // with enough tiles for two workgroups per CU, four waves each: the two share the CU's LDS, so one's
+    // prologue and epilogue no longer wait for the other's to finish
+    if (D.J == 1 && D.nib <= 2 && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
+      return launch_spmm<2, Q, 4, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (D.J == 1 && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
       return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);

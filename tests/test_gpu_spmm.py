@@ -73,6 +73,20 @@ def test_spmm_full_size_configs(name, B):
         assert rel_fro(got[r], want[r]) <= 10 * TOL["bf16"]
 
 
+@pytest.mark.parametrize("m,n,B,n_in,S", [(16384, 256, 256, 8, None), (16390, 200, 248, 8, None), (12288, 320, 384, 16, None),
+                                          (12290, 256, 376, 24, None), (16384, 192, 256, 8, 0.8)])
+def test_tall_matrix_many_columns(m, n, B, n_in, S):
+    """At least 512 tiles of 128 rows x 64 columns: the launches with 128-row tiles (four waves per workgroup and
+    two workgroups per CU for n_in <= 16, eight waves otherwise).  Ragged rows, columns and batch; a short
+    reduction (3 to 5 slices over 4 or 8 waves: some waves get none)."""
+    got, want = _run("large_q1", m, n, B, "bf16", S=S, n_in=n_in)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL["bf16"]
+    rows = np.random.default_rng(B).integers(0, got.shape[0], size=64)
+    for r in rows:
+        assert rel_fro(got[r], want[r]) <= 10 * TOL["bf16"]
+
+
 @pytest.mark.parametrize("B,dtype", [(1, "bf16"), (8, "bf16"), (64, "bf16"), (200, "bf16"), (16, "f32")])
 def test_many_patches_per_unit(B, dtype):
     """Pruning rate 0.75 with n_in = 8: about 16 care bits per slice against 8 encrypted bits, so most
