@@ -913,6 +913,11 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     if (!x_fast) return launch_spmm<2, Q, 1, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     // two slice buffers per wave leave no room for the tables of multi-word slices
     if (D.J > 1) return launch_spmm<2, Q, 1, false, 8, 1, 1, 4>(D, X, ldx, B, Y, ldy, x_fast, st);
+    // 64-row tiles once they fill the chip: X is re-read half as often; with enough of them, four-wave
+    // workgroups that run two per CU
+    const int64_t tiles64 = (int64_t)((D.nrb + 1) / 2) * ((B + 63) / 64);
+    if (D.nib <= 2 && tiles64 >= 512) return launch_spmm<2, Q, 2, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (tiles64 >= 200) return launch_spmm<2, Q, 2, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 1, false, 8, 2, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 3) {
     return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);

@@ -73,13 +73,16 @@ def test_spmm_full_size_configs(name, B):
         assert rel_fro(got[r], want[r]) <= 10 * TOL["bf16"]
 
 
-@pytest.mark.parametrize("m,n,B,n_in,S", [(16384, 256, 256, 8, None), (16390, 200, 248, 8, None), (12288, 320, 384, 16, None),
-                                          (12290, 256, 376, 24, None), (16384, 192, 256, 8, 0.8)])
-def test_tall_matrix_many_columns(m, n, B, n_in, S):
-    """At least 512 tiles of 128 rows x 64 columns: the launches with 128-row tiles (four waves per workgroup and
-    two workgroups per CU for n_in <= 16, eight waves otherwise).  Ragged rows, columns and batch; a short
-    reduction (3 to 5 slices over 4 or 8 waves: some waves get none)."""
-    got, want = _run("large_q1", m, n, B, "bf16", S=S, n_in=n_in)
+@pytest.mark.parametrize("name,m,n,B,n_in,S", [
+    ("large_q1", 16384, 256, 256, 8, None), ("large_q1", 16390, 200, 248, 8, None), ("large_q1", 12288, 320, 384, 16, None),
+    ("large_q1", 12290, 256, 376, 24, None), ("large_q1", 16384, 192, 256, 8, 0.8),
+    ("large_q2", 16390, 200, 136, 16, None), ("large_q2", 12810, 320, 64, 8, None), ("large_q2", 8200, 256, 256, 24, 0.85)])
+def test_tall_matrix_many_columns(name, m, n, B, n_in, S):
+    """Enough tiles to fill the chip once or twice: the launches with 128-row tiles (one plane) or 64-row tiles
+    (two planes), with four waves per workgroup and two workgroups per CU from 512 tiles on (n_in <= 16) and
+    eight waves otherwise.  Ragged rows, columns and batch; a short reduction (3 to 5 slices over 4 or 8 waves:
+    some waves get none)."""
+    got, want = _run(name, m, n, B, "bf16", S=S, n_in=n_in)
     assert np.isfinite(got).all()
     assert rel_fro(got, want) <= TOL["bf16"]
     rows = np.random.default_rng(B).integers(0, got.shape[0], size=64)
