@@ -90,7 +90,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
   constexpr int RSB = XDIR ? CW * 2 : CW * 2 + 16;  // LDS row stride in bytes
   constexpr int XSL = 64 * RSB;                     // the 64 X rows of one slice
   constexpr int KC = RB * (1 + Q * (NIBT == 3 ? 2 : 1));  // compressed dwords per lane and slice (XDIR)
-  constexpr int CSL = KC * 256;                           // their staging area for one slice (XDIR)
+  // With one slice buffer the staging area also takes the patch offsets of the wave's range (one dword
+  // per lane, row block and plane), fetched ahead of everything else.
+  constexpr bool OFF_DMA = XDIR && PD == 1;
+  constexpr int KO = OFF_DMA ? RB * Q : 0;
+  constexpr int CSL = (KC + KO) * 256;                    // staging area of one slice (XDIR)
   constexpr int XBUF = XDIR ? PD * (XSL + CSL) : XSL;     // one wave's LDS share (PD slice buffers)
   constexpr int ROWS = 32 * RB;
   constexpr int NR = XF32 ? CW / 3 : CW;       // real X columns per workgroup
@@ -371,6 +375,23 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
 
   // ---- first loads go out before anything else so that they overlap the table build
   Comp ring[2];
+  const bool pre_ok = cnt <= 63;  // uniform: lane i can hold the patch offset of unit i of the range
+  if constexpr (OFF_DMA) {
+    // The patch offsets go first: their answer starts the only dependent read of the prologue (the patch
+    // entries), which then overlaps the arrival of the first slice instead of following it.
+    if (cnt > 0 && pre_ok) {
+      const u32x4 odesc = {(uint32_t)reinterpret_cast<uint64_t>(l_patch_off),
+                           (uint32_t)(reinterpret_cast<uint64_t>(l_patch_off) >> 32) & 0xffffu,
+                           (uint32_t)(((int64_t)l_q * l_n_units + 1) * 4), kRsrcFlags};
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int p = 0; p < Q; ++p) {
+          const uint32_t u0 = (uint32_t)(p * l_n_units + (blockIdx.x * RB + rb) * l_spr + w0);  // uniform
+          dma_dword(cbuf_lds + (KC + rb * Q + p) * 256, (uint32_t)(lane * 4), odesc, u0 * 4u);
+        }
+    }
+  }
   if constexpr (XDIR) {
     if (cnt > 0) {
       load_comp_hidden(w0, 0);
@@ -394,17 +415,18 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
     }
   }
   // patch offsets of the whole range: lane i holds the offset of unit i of the range
-  const bool pre_ok = cnt <= 63;  // uniform
   uint32_t offv[RB][Q];
+  if constexpr (!OFF_DMA) {
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int rbg = blockIdx.x * RB + rb;
+    for (int rb = 0; rb < RB; ++rb) {
+      const int rbg = blockIdx.x * RB + rb;
 #pragma unroll
-    for (int p = 0; p < Q; ++p) {
-      offv[rb][p] = 0u;
-      if (rbg < l_nrb && pre_ok && cnt > 0) {
-        const uint32_t *po = l_patch_off + ((int64_t)p * l_n_units + (int64_t)rbg * l_spr + w0);
-        if (lane <= cnt) offv[rb][p] = po[lane];
+      for (int p = 0; p < Q; ++p) {
+        offv[rb][p] = 0u;
+        if (rbg < l_nrb && pre_ok && cnt > 0) {
+          const uint32_t *po = l_patch_off + ((int64_t)p * l_n_units + (int64_t)rbg * l_spr + w0);
+          if (lane <= cnt) offv[rb][p] = po[lane];
+        }
       }
     }
   }
@@ -450,6 +472,24 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
   }
   if constexpr (!PRIV_LUT) __syncthreads();
 
+  if constexpr (OFF_DMA) {
+    // the offsets were the first loads of the wave: everything younger (the NGRP loads of the first slice)
+    // may still be in flight
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int p = 0; p < Q; ++p) offv[rb][p] = 0u;
+    if (cnt > 0 && pre_ok) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NGRP) : "memory");
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int p = 0; p < Q; ++p) {
+          const uint32_t v = cbuf[(KC + rb * Q + p) * 64 + lane];
+          if (blockIdx.x * RB + rb < l_nrb && lane <= cnt) offv[rb][p] = v;
+        }
+    }
+  }
   // ---- patch entries of the range: lane j holds the j-th entry (relative to the range start).
   // A range with more than 63 units or more than 64 entries of one (row block, plane) reads its
   // lists from memory inside the loop instead.
