@@ -50,6 +50,23 @@ SMALL_CASES = [
 ]
 
 
+EDGE_CASES = [
+    ("tiny", 1, 1, 1, "f32"), ("tiny", 1, 1, 1, "bf16"), ("tiny", 1, 1, 8, "bf16"), ("tiny", 31, 63, 2, "bf16"),
+    ("fig1", 40, 130, 1000, "bf16"), ("fig1", 40, 130, 1024, "bf16"), ("large_q1", 4100, 64, 512, "bf16"),
+    ("large_q2", 4100, 64, 512, "bf16"), ("lstm", 70, 64, 264, "f32"), ("fc6", 2, 9216, 8, "bf16"),
+]
+
+
+@pytest.mark.parametrize("name,m,n,B,dtype", EDGE_CASES)
+def test_spmm_degenerate_and_extreme_shapes(name, m, n, B, dtype):
+    """One weight; fewer rows than a row block and fewer columns than a slice; many more columns of X than a
+    workgroup covers; a single slice (most waves of a workgroup get nothing); two rows with a long reduction."""
+    got, want = _run(name, m, n, B, dtype)
+    assert got.shape == want.shape == (m, B)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("name,m,n,B,dtype", SMALL_CASES)
 def test_spmm_matches_fp64_oracle(name, m, n, B, dtype):
     got, want = _run(name, m, n, B, dtype)
