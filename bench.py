@@ -336,7 +336,11 @@ def main():
                "tflops": flops * steps / wall / 1e12, "compressed_gbs": runner.comp_bytes * steps / wall / 1e9,
                "replicas": runner.R, "step_bytes": runner.step_bytes, "compressed_bytes": runner.comp_bytes,
                "roofline": roofline_entry(flops, runner.comp_bytes, runner.step_bytes, ev / steps, B)}
-        res["roofline"]["traffic"] = MEASURED_TRAFFIC.get(f"{cfg.name}:B{B}")
+        tr = MEASURED_TRAFFIC.get(f"{cfg.name}:B{B}")
+        if tr is not None:      # HBM bytes per launch (read + written), rocprofv3 counters scaled by a known copy
+            res["roofline"]["traffic"] = tr["read_bytes"] + tr["write_bytes"]
+            res["roofline"]["traffic_read_bytes"] = tr["read_bytes"]
+            res["roofline"]["traffic_write_bytes"] = tr["write_bytes"]
         return res, runner, xexact
 
     main_res, runner, xexact = measure(args.batch, args.steps, args.warmup)
