@@ -939,7 +939,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
       if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
       return launch_spmm<2, Q, 2, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     }
-    if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (blocks == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
     // with enough tiles for two workgroups per CU, four waves each: the two share the CU's LDS, so one's
     // prologue and epilogue no longer wait for the other's to finish
@@ -947,8 +947,9 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
       return launch_spmm<2, Q, 4, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (D.J == 1 && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
       return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
-    return launch_spmm<2, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    return launch_spmm<2, Q, 2, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
+    if (blocks == 1 && x_fast) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (!x_fast) return launch_spmm<2, Q, 1, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     // two slice buffers per wave leave no room for the tables of multi-word slices
