@@ -163,8 +163,8 @@ MEASURED_TRAFFIC = {
     # profiles/spmm_large_q1_hbm_traffic.md: bytes read + written per launch
     "large_q1:B1": {"read_bytes": 9.98e6, "write_bytes": 0.07e6},
     "large_q1:B8": {"read_bytes": 10.48e6, "write_bytes": 0.52e6},
-    "large_q1:B64": {"read_bytes": 14.17e6, "write_bytes": 4.19e6},
-    "large_q1:B256": {"read_bytes": 26.77e6, "write_bytes": 16.78e6},
+    "large_q1:B64": {"read_bytes": 14.16e6, "write_bytes": 4.19e6},
+    "large_q1:B256": {"read_bytes": 26.75e6, "write_bytes": 16.78e6},
 }
 
 
