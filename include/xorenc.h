@@ -36,7 +36,7 @@ extern "C" {
 #define XORENC_API
 #endif
 
-#define XORENC_VERSION 0x00020000u
+#define XORENC_VERSION 0x00020100u
 
 enum {
   XORENC_OK = 0,
