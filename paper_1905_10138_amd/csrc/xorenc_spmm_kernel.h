@@ -915,8 +915,15 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
       if (!wide) switch (D.nib) {
           case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
           case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-          case 3: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-          default: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 3:
+            // (the four-wave workgroups that share a CU have LDS for one or two tables per wave only)
+            if constexpr (NW == 4 && !XF32) return XORENC_EUNSUPPORTED;
+            else launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+            break;
+          default:
+            if constexpr (NW == 4 && !XF32) return XORENC_EUNSUPPORTED;
+            else launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+            break;
         }
   }
   return xorenc_internal_check_launch();
