@@ -65,92 +65,148 @@ int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// decode kernel: one slot (row, slice) per lane
+// decode kernel.  Phase 1: one slot (row, 64-bit word of a row) per lane: table look-ups, patch
+// flips, mask.  Bit-plane output stores the word.  Dense output, phase 2: the 256 words of the
+// workgroup's run (eight units: 32 rows x eight consecutive word positions when the run does not cross
+// a row block) are parked in LDS and expanded with eight consecutive columns per lane, a wave's 64 lanes
+// covering the eight units of one row: one store instruction then writes up to 512 consecutive
+// columns of a row.  A workgroup builds the tables once and walks over `chunks` runs of 256 slots.
 
-__global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, void *out, int64_t ld) {
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+struct SlotStage {                       // phase-1 result of one slot, as phase 2 reads it
+  uint8_t keep[8];                       // byte c = mask bits of columns 8c .. 8c+7
+  uint8_t w[XORENC_MAX_Q][8];            // the same bytes of each plane's decrypted, patched word
+  float a[XORENC_MAX_Q];
+};
+
+__global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, void *out, int64_t ld, int chunks) {
   __shared__ uint32_t lut[XORENC_MAX_J * (XORENC_MAX_N_IN / 8) * 512];
+  __shared__ __attribute__((aligned(8))) SlotStage stage[256];
   build_xor_tables(lut, L);
   __syncthreads();
 
   const int lane = threadIdx.x & 63;
-  const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const bool valid = slot < L.n_slots;
-  const int64_t u = valid ? (slot >> 5) : 0;
-  const int rr = (int)(slot & 31);
-  const int rb = (int)(u / L.spr), s = (int)(u % L.spr);
-  const int r = valid ? rb * 32 + rr : L.m;  // invalid lanes behave like a padding row
-  const uint64_t keep =
-      valid ? ((uint64_t)L.mask32[2 * slot] | ((uint64_t)L.mask32[2 * slot + 1] << 32)) : 0ull;
+  for (int ch = 0; ch < chunks; ++ch) {
+    const int64_t chunk0 = ((int64_t)blockIdx.x * chunks + ch) * 256;
+    if (chunk0 >= L.n_slots) break;  // uniform
+    const int64_t slot = chunk0 + threadIdx.x;
+    const bool valid = slot < L.n_slots;
+    const int u = valid ? (int)(slot >> 5) : 0;  // n_units < 2^31 (checked on the host)
+    const int rr = (int)(slot & 31);
+    const int rb = u / L.spr, s = u % L.spr;
+    const int r = valid ? rb * 32 + rr : L.m;  // invalid lanes behave like a padding row
+    const uint64_t keep =
+        valid ? ((uint64_t)L.mask32[2 * slot] | ((uint64_t)L.mask32[2 * slot + 1] << 32)) : 0ull;
 
-  uint64_t w[XORENC_MAX_Q];
-  float a[XORENC_MAX_Q];
+    uint64_t w[XORENC_MAX_Q];
+    float a[XORENC_MAX_Q];
 #pragma unroll
-  for (int p = 0; p < XORENC_MAX_Q; ++p) {
-    w[p] = 0;
-    a[p] = 0.f;
-    if (p < L.q && valid) {
-      // word s of the row belongs to slice s / J and is word s % J of it
-      const int64_t eslot = ((int64_t)rb * L.espr + s / L.J) * 32 + rr;
-      const int wsel = s % L.J;
-      const uint32_t x = load_enc(L.enc, (int64_t)p * L.n_eslots + eslot, L.n_in);
-      uint32_t lo = 0, hi = 0;
-      for (int b = 0; b < L.nib; ++b) {
-        const int e = ((wsel * L.nib + b) << 8) + ((x >> (8 * b)) & 255);
-        lo ^= lut[2 * e];
-        hi ^= lut[2 * e + 1];
+    for (int p = 0; p < XORENC_MAX_Q; ++p) {
+      w[p] = 0;
+      a[p] = 0.f;
+      if (p < L.q && valid) {
+        // word s of the row belongs to slice s / J and is word s % J of it
+        const int64_t eslot = ((int64_t)rb * L.espr + s / L.J) * 32 + rr;
+        const int wsel = s % L.J;
+        const uint32_t x = load_enc(L.enc, (int64_t)p * L.n_eslots + eslot, L.n_in);
+        uint32_t lo = 0, hi = 0;
+        for (int b = 0; b < L.nib; ++b) {
+          const int e = ((wsel * L.nib + b) << 8) + ((x >> (8 * b)) & 255);
+          lo ^= lut[2 * e];
+          hi ^= lut[2 * e + 1];
+        }
+        uint64_t dec = (uint64_t)lo | ((uint64_t)hi << 32);
+        const uint32_t pa = L.patch_off[(int64_t)p * L.n_units + u];
+        const uint32_t pe = L.patch_off[(int64_t)p * L.n_units + u + 1];
+        for (uint32_t i = pa; i < pe; ++i) {
+          const uint32_t v = L.patch[i];
+          if ((int)(v >> 6) == rr) dec ^= 1ull << (v & 63);
+        }
+        w[p] = dec & keep;
+        if (r < L.m) a[p] = L.alpha[(int64_t)p * L.m + r];
       }
-      uint64_t dec = (uint64_t)lo | ((uint64_t)hi << 32);
-      const uint32_t pa = L.patch_off[(int64_t)p * L.n_units + u];
-      const uint32_t pe = L.patch_off[(int64_t)p * L.n_units + u + 1];
-      for (uint32_t i = pa; i < pe; ++i) {
-        const uint32_t v = L.patch[i];
-        if ((int)(v >> 6) == rr) dec ^= 1ull << (v & 63);
-      }
-      w[p] = dec & keep;
-      if (r < L.m) a[p] = L.alpha[(int64_t)p * L.m + r];
     }
-  }
 
-  if (out_kind == XORENC_OUT_PLANES) {
-    if (r < L.m) {
-      uint64_t *o = static_cast<uint64_t *>(out);
-      const int64_t l = (int64_t)L.m * L.spr;
+    if (out_kind == XORENC_OUT_PLANES) {
+      if (r < L.m) {
+        uint64_t *o = static_cast<uint64_t *>(out);
+        const int64_t l = (int64_t)L.m * L.spr;
 #pragma unroll
-      for (int p = 0; p < XORENC_MAX_Q; ++p)
-        if (p < L.q) o[(int64_t)p * l + (int64_t)r * L.spr + s] = w[p];
+        for (int p = 0; p < XORENC_MAX_Q; ++p)
+          if (p < L.q) o[(int64_t)p * l + (int64_t)r * L.spr + s] = w[p];
+      }
+      continue;
     }
-    return;
-  }
 
-  // dense output: the wave walks over its 64 slots; for slot j every lane writes one column,
-  // so each store instruction covers 64 consecutive elements of one row.
-  const uint32_t keep_lo = (uint32_t)keep, keep_hi = (uint32_t)(keep >> 32);
-  for (int j = 0; j < 64; ++j) {
-    const int rj = __builtin_amdgcn_readlane(r, j);
-    if (rj >= L.m) continue;  // uniform
-    const int sj = __builtin_amdgcn_readlane(s, j);
-    const uint32_t klo = __builtin_amdgcn_readlane(keep_lo, j), khi = __builtin_amdgcn_readlane(keep_hi, j);
-    const uint64_t kj = (uint64_t)klo | ((uint64_t)khi << 32);
-    const int col = sj * 64 + lane;
-    float v = 0.f;
-    const bool kept = (kj >> lane) & 1;
+    // ---- dense output.  Park the slot for the other waves of the workgroup.
+    SlotStage &mine = stage[threadIdx.x];
+    *reinterpret_cast<uint64_t *>(mine.keep) = keep;
 #pragma unroll
     for (int p = 0; p < XORENC_MAX_Q; ++p)
       if (p < L.q) {
-        const uint32_t wlo = __builtin_amdgcn_readlane((uint32_t)w[p], j);
-        const uint32_t whi = __builtin_amdgcn_readlane((uint32_t)(w[p] >> 32), j);
-        const float aj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(a[p]), j));
-        const uint64_t wj = (uint64_t)wlo | ((uint64_t)whi << 32);
-        const float term = ((wj >> lane) & 1) ? aj : -aj;
-        v = (p == 0) ? term : v + term;  // ((+-a1) + (+-a2)) + ... left to right in fp32
+        *reinterpret_cast<uint64_t *>(mine.w[p]) = w[p];
+        mine.a[p] = a[p];
       }
-    if (!kept) v = 0.f;
-    if (col < L.n) {
-      if (out_kind == XORENC_OUT_F32)
-        static_cast<float *>(out)[(int64_t)rj * ld + col] = v;
-      else
-        static_cast<uint16_t *>(out)[(int64_t)rj * ld + col] = (uint16_t)f32_to_bf16_rne(v);
+    __syncthreads();
+    // wave v takes rows 8v .. 8v+7 of the run's units; lane = (unit of the run, group of eight columns)
+    const int un = lane >> 3, cg = lane & 7;
+    const int64_t ul = (chunk0 >> 5) + un;       // this lane's unit (runs start at a multiple of 8 units)
+    const bool unit_ok = ul < (int64_t)L.n_units;
+    const int uj = unit_ok ? (int)ul : 0;
+    const int row_base = (uj / L.spr) * 32;
+    const int col = (uj % L.spr) * 64 + 8 * cg;
+    for (int i = 0; i < 8; ++i) {
+      const int row = 8 * (threadIdx.x >> 6) + i;
+      const int j = un * 32 + row;  // slot of the run
+      const int rj = row_base + row;
+      if (!unit_ok || rj >= L.m || col >= L.n) continue;
+      const SlotStage &st = stage[j];
+      const uint32_t kb = st.keep[cg];
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = 0.f;
+#pragma unroll
+      for (int p = 0; p < XORENC_MAX_Q; ++p)
+        if (p < L.q) {  // uniform
+          const uint32_t wb = st.w[p][cg];
+          const uint32_t ap = __float_as_uint(st.a[p]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            // bit 1 -> +alpha, bit 0 -> -alpha: flip the sign bit where the bit is 0
+            const float term = __uint_as_float(ap ^ ((~wb >> e) << 31));
+            v[e] = (p == 0) ? term : v[e] + term;  // ((+-a1) + (+-a2)) + ... left to right in fp32
+          }
+        }
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (!((kb >> e) & 1u)) v[e] = 0.f;  // pruned -> +0.0
+      const int nvalid = min(8, L.n - col);  // columns of this lane inside the matrix
+      if (out_kind == XORENC_OUT_F32) {
+        float *dst = static_cast<float *>(out) + (int64_t)rj * ld + col;
+        if (nvalid == 8 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+          reinterpret_cast<float4 *>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
+          reinterpret_cast<float4 *>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+          for (int e = 0; e < nvalid; ++e) dst[e] = v[e];
+        }
+      } else {
+        uint32_t pk[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const f32x2_t two = {v[2 * e], v[2 * e + 1]};
+          pk[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));  // round to nearest even
+        }
+        uint16_t *dst = static_cast<uint16_t *>(out) + (int64_t)rj * ld + col;
+        if (nvalid == 8 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+          *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        } else {
+          for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(pk[e >> 1] >> (16 * (e & 1)));
+        }
+      }
     }
+    __syncthreads();  // the stage entries are rewritten in the next run
   }
 }
 
@@ -170,9 +226,13 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   if (out_kind != XORENC_OUT_PLANES && ld_out < layer->n) return XORENC_EINVAL;
   const uintptr_t al = out_kind == XORENC_OUT_PLANES ? 7 : (out_kind == XORENC_OUT_F32 ? 3 : 1);
   if ((uintptr_t)out & al) return XORENC_EALIGN;
-  const unsigned blocks = (unsigned)((D.n_slots + 255) / 256);
+  // a few workgroups per CU, each walking over several runs of 256 slots, so that the tables are built
+  // a few thousand times less often than there are runs
+  const int64_t runs = (D.n_slots + 255) / 256;
+  const int chunks = (int)((runs + 2047) / 2048);
+  const unsigned blocks = (unsigned)((runs + chunks - 1) / chunks);
   hipLaunchKernelGGL(decode_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), D, out_kind,
-                     out, ld_out);
+                     out, ld_out, chunks);
   return xorenc_internal_check_launch();
 }
 
