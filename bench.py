@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--replica-bytes", type=float, default=float(1 << 30))
     ap.add_argument("--decode-only", action="store_true", help="also time xorenc_decode (planes) on the workload")
     ap.add_argument("--no-wide", action="store_true", help="skip the n_out=192 / n_in=24 extra on the same matrix")
+    ap.add_argument("--no-decode", action="store_true", help="skip the timing of xorenc_decode on the workload")
     ap.add_argument("--no-encoder", action="store_true", help="skip the timing of the two GPU encoders")
     ap.add_argument("--no-fig1", action="store_true", help="skip the Fig. 1-shaped extra (decode-only and fused, B=64)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -224,6 +225,27 @@ def fig1_extra(xe, torch, dev, args):
     return res
 
 
+def decode_extra(xe, torch, layer, reps=50):
+    """xorenc_decode on the main workload's layer: bit-planes, dense bf16 and dense fp32.  Bytes = compressed
+    bytes read + output bytes written; the fraction is against 8 TB/s."""
+    res = {}
+    for kind, name in ((xe.OUT_PLANES, "planes"), (xe.OUT_BF16, "bf16"), (xe.OUT_F32, "f32")):
+        out = xe.decode(layer, kind)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            xe.decode(layer, kind, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        nbytes = layer.compressed_bytes() + out.numel() * out.element_size()
+        res[name] = {"us": us, "bytes": nbytes, "gbs": nbytes / (us * 1e-6) / 1e9,
+                     "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del out
+    return res
+
+
 def wide_extra(xe, torch, dev, args, base_cfg, n_in=24):
     """The default workload re-encoded with slices of 192 bits and n_in = 24 or 20 (the region where the
     paper reports its best ratios, Section 3.3): same or fewer bits per weight for the encrypted stream,
@@ -389,6 +411,8 @@ def main():
         extra["n_out_192"] = wide_extra(xe, torch, dev, args, cfg)
         extra["n_out_192_n_in_20"] = wide_extra(xe, torch, dev, args, cfg, n_in=20)
     extra["storage"] = storage_extra(xe, layer)
+    if not args.no_decode:
+        extra["decode"] = decode_extra(xe, torch, layer)
     if not args.no_encoder:
         extra["encoder"] = encoder_extra(xe, torch, dev, cfg)
     if args.copy_calibration:

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
           if ((int)(v >> 6) == rr) dec ^= 1ull << (v & 63);
         }
         w[p] = dec & keep;
-        if (r < L.m) a[p] = L.alpha[(int64_t)p * L.m + r];
+        if (out_kind != XORENC_OUT_PLANES && r < L.m) a[p] = L.alpha[(int64_t)p * L.m + r];
       }
     }
 
@@ -226,10 +226,11 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   if (out_kind != XORENC_OUT_PLANES && ld_out < layer->n) return XORENC_EINVAL;
   const uintptr_t al = out_kind == XORENC_OUT_PLANES ? 7 : (out_kind == XORENC_OUT_F32 ? 3 : 1);
   if ((uintptr_t)out & al) return XORENC_EALIGN;
-  // a few workgroups per CU, each walking over several runs of 256 slots, so that the tables are built
-  // a few thousand times less often than there are runs
+  // at most a few thousand workgroups, each walking over several runs of 256 slots, so that the tables
+  // are not built once per run
   const int64_t runs = (D.n_slots + 255) / 256;
-  const int chunks = (int)((runs + 2047) / 2048);
+  const int64_t wgs = out_kind == XORENC_OUT_F32 ? 4096 : 2048;  // measured: fp32 stores like more of them in flight
+  const int chunks = (int)((runs + wgs - 1) / wgs);
   const unsigned blocks = (unsigned)((runs + chunks - 1) / chunks);
   hipLaunchKernelGGL(decode_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), D, out_kind,
                      out, ld_out, chunks);
