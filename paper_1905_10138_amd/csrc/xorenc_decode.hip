@@ -170,18 +170,18 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
 #pragma unroll
       for (int p = 0; p < XORENC_MAX_Q; ++p)
         if (p < L.q) {  // uniform
-          const uint32_t wb = st.w[p][cg];
+          const uint32_t nw = ~(uint32_t)st.w[p][cg];
           const uint32_t ap = __float_as_uint(st.a[p]);
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             // bit 1 -> +alpha, bit 0 -> -alpha: flip the sign bit where the bit is 0
-            const float term = __uint_as_float(ap ^ ((~wb >> e) << 31));
+            const float term = __uint_as_float(ap ^ ((nw << (31 - e)) & 0x80000000u));
             v[e] = (p == 0) ? term : v[e] + term;  // ((+-a1) + (+-a2)) + ... left to right in fp32
           }
         }
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (!((kb >> e) & 1u)) v[e] = 0.f;  // pruned -> +0.0
+      for (int e = 0; e < 8; ++e)  // pruned -> +0.0: AND with 0 or all ones (sign-extended mask bit)
+        v[e] = __uint_as_float(__float_as_uint(v[e]) & (uint32_t)__builtin_amdgcn_sbfe((int)kb, e, 1));
       const int nvalid = min(8, L.n - col);  // columns of this lane inside the matrix
       if (out_kind == XORENC_OUT_F32) {
         float *dst = static_cast<float *>(out) + (int64_t)rj * ld + col;
