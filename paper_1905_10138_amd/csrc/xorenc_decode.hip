@@ -82,7 +82,7 @@ struct SlotStage {                       // phase-1 result of one slot, as phase
 };
 
 __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, void *out, int64_t ld, int chunks) {
-  __shared__ uint32_t lut[XORENC_MAX_J * (XORENC_MAX_N_IN / 8) * 512];
+  extern __shared__ __attribute__((aligned(8))) uint32_t lut[];  // J * nib tables of 256 x 8 bytes (launch sizes it)
   __shared__ __attribute__((aligned(8))) SlotStage stage[256];
   build_xor_tables(lut, L);
   __syncthreads();
@@ -150,62 +150,73 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
         mine.a[p] = a[p];
       }
     __syncthreads();
-    // wave v takes rows 8v .. 8v+7 of the run's units; lane = (unit of the run, group of eight columns)
-    const int un = lane >> 3, cg = lane & 7;
-    const int64_t ul = (chunk0 >> 5) + un;       // this lane's unit (runs start at a multiple of 8 units)
-    const bool unit_ok = ul < (int64_t)L.n_units;
-    const int uj = unit_ok ? (int)ul : 0;
-    const int row_base = (uj / L.spr) * 32;
-    const int col = (uj % L.spr) * 64 + 8 * cg;
-    for (int i = 0; i < 8; ++i) {
-      const int row = 8 * (threadIdx.x >> 6) + i;
-      const int j = un * 32 + row;  // slot of the run
-      const int rj = row_base + row;
-      if (!unit_ok || rj >= L.m || col >= L.n) continue;
-      const SlotStage &st = stage[j];
-      const uint32_t kb = st.keep[cg];
-      float v[8];
+    // wave v takes rows 8v .. 8v+7 of the run's units.  A lane writes 16 bytes per store: eight bf16 or
+    // four fp32 columns; the 64 lanes of a store cover consecutive column groups of consecutive units
+    // (bf16: all eight units in one pass; fp32: four units per pass, two passes).
+    auto expand_rows = [&](auto epl_tag) {
+      constexpr int EPL = decltype(epl_tag)::value;  // elements per lane and store
+      constexpr int G = 64 / EPL;                    // column groups per unit
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = 0.f;
+      for (int pass = 0; pass < 8 / EPL; ++pass) {
+        const int idx = 64 * pass + lane;
+        const int un = idx / G, g = idx % G;
+        const int64_t ul = (chunk0 >> 5) + un;  // this lane's unit (runs start at a multiple of 8 units)
+        const bool unit_ok = ul < (int64_t)L.n_units;
+        const int uj = unit_ok ? (int)ul : 0;
+        const int row_base = (uj / L.spr) * 32;
+        const int col = (uj % L.spr) * 64 + EPL * g;
+        const int byte = (EPL * g) >> 3, shift = (EPL * g) & 7;
+        for (int i = 0; i < 8; ++i) {
+          const int row = 8 * (threadIdx.x >> 6) + i;
+          const int rj = row_base + row;
+          if (!unit_ok || rj >= L.m || col >= L.n) continue;
+          const SlotStage &st = stage[un * 32 + row];
+          const uint32_t kb = (uint32_t)st.keep[byte] >> shift;
+          float v[EPL];
 #pragma unroll
-      for (int p = 0; p < XORENC_MAX_Q; ++p)
-        if (p < L.q) {  // uniform
-          const uint32_t nw = ~(uint32_t)st.w[p][cg];
-          const uint32_t ap = __float_as_uint(st.a[p]);
+          for (int e = 0; e < EPL; ++e) v[e] = 0.f;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            // bit 1 -> +alpha, bit 0 -> -alpha: flip the sign bit where the bit is 0
-            const float term = __uint_as_float(ap ^ ((nw << (31 - e)) & 0x80000000u));
-            v[e] = (p == 0) ? term : v[e] + term;  // ((+-a1) + (+-a2)) + ... left to right in fp32
+          for (int p = 0; p < XORENC_MAX_Q; ++p)
+            if (p < L.q) {  // uniform
+              const uint32_t nw = ~((uint32_t)st.w[p][byte] >> shift);
+              const uint32_t ap = __float_as_uint(st.a[p]);
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) {
+                // bit 1 -> +alpha, bit 0 -> -alpha: flip the sign bit where the bit is 0
+                const float term = __uint_as_float(ap ^ ((nw << (31 - e)) & 0x80000000u));
+                v[e] = (p == 0) ? term : v[e] + term;  // ((+-a1) + (+-a2)) + ... left to right in fp32
+              }
+            }
+#pragma unroll
+          for (int e = 0; e < EPL; ++e)  // pruned -> +0.0: AND with 0 or all ones (sign-extended mask bit)
+            v[e] = __uint_as_float(__float_as_uint(v[e]) & (uint32_t)__builtin_amdgcn_sbfe((int)kb, e, 1));
+          const int nvalid = min(EPL, L.n - col);  // columns of this lane inside the matrix
+          if constexpr (EPL == 4) {
+            float *dst = static_cast<float *>(out) + (int64_t)rj * ld + col;
+            if (nvalid == 4 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0)
+              *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            else
+              for (int e = 0; e < nvalid; ++e) dst[e] = v[e];
+          } else {
+            uint32_t pk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const f32x2_t two = {v[2 * e], v[2 * e + 1]};
+              pk[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));  // round to nearest even
+            }
+            uint16_t *dst = static_cast<uint16_t *>(out) + (int64_t)rj * ld + col;
+            if (nvalid == 8 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0)
+              *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            else
+              for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(pk[e >> 1] >> (16 * (e & 1)));
           }
         }
-#pragma unroll
-      for (int e = 0; e < 8; ++e)  // pruned -> +0.0: AND with 0 or all ones (sign-extended mask bit)
-        v[e] = __uint_as_float(__float_as_uint(v[e]) & (uint32_t)__builtin_amdgcn_sbfe((int)kb, e, 1));
-      const int nvalid = min(8, L.n - col);  // columns of this lane inside the matrix
-      if (out_kind == XORENC_OUT_F32) {
-        float *dst = static_cast<float *>(out) + (int64_t)rj * ld + col;
-        if (nvalid == 8 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
-          reinterpret_cast<float4 *>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
-          reinterpret_cast<float4 *>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
-        } else {
-          for (int e = 0; e < nvalid; ++e) dst[e] = v[e];
-        }
-      } else {
-        uint32_t pk[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const f32x2_t two = {v[2 * e], v[2 * e + 1]};
-          pk[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));  // round to nearest even
-        }
-        uint16_t *dst = static_cast<uint16_t *>(out) + (int64_t)rj * ld + col;
-        if (nvalid == 8 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
-          *reinterpret_cast<uint4 *>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        } else {
-          for (int e = 0; e < nvalid; ++e) dst[e] = (uint16_t)(pk[e >> 1] >> (16 * (e & 1)));
-        }
       }
-    }
+    };
+    if (out_kind == XORENC_OUT_F32)
+      expand_rows(std::integral_constant<int, 4>{});
+    else
+      expand_rows(std::integral_constant<int, 8>{});
     __syncthreads();  // the stage entries are rewritten in the next run
   }
 }
@@ -232,8 +243,9 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   const int64_t wgs = out_kind == XORENC_OUT_F32 ? 4096 : 2048;  // measured: fp32 stores like more of them in flight
   const int chunks = (int)((runs + wgs - 1) / wgs);
   const unsigned blocks = (unsigned)((runs + chunks - 1) / chunks);
-  hipLaunchKernelGGL(decode_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), D, out_kind,
-                     out, ld_out, chunks);
+  const size_t lut_bytes = (size_t)D.J * D.nib * 2048;  // small tables leave LDS for eight workgroups per CU
+  hipLaunchKernelGGL(decode_kernel, dim3(blocks), dim3(256), lut_bytes, static_cast<hipStream_t>(hip_stream), D,
+                     out_kind, out, ld_out, chunks);
   return xorenc_internal_check_launch();
 }
 
