@@ -70,6 +70,36 @@ def test_wide_slices_planes_and_dense_bit_exact(name, m, n, n_out, n_in):
     assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(dense))
 
 
+def _random_geometries(count, seed):
+    rng = np.random.default_rng(seed)
+    names = ["tiny", "fig1", "fc6", "lstm", "large_q1", "large_q2"]
+    return [(names[int(rng.integers(len(names)))], int(rng.integers(1, 400)), int(rng.integers(1, 2000)),
+             int(rng.choice([64, 64, 128, 192, 256])), int(rng.integers(4, 33)), int(rng.choice([0, 0, 1, 3, 8])))
+            for _ in range(count)]
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,pad", _random_geometries(24, 77))
+def test_random_geometries_dense_and_planes(name, m, n, n_out, n_in, pad):
+    """Seeded random shapes: ragged rows and columns (partial 16-byte stores at the row ends), every slice width,
+    any n_in, outputs with a padded leading dimension (unaligned rows take the element-wise store path)."""
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc, L = _gpu_layer(name, m, n, n_out, n_in)
+    got = xe.decode(L, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
+    assert np.array_equal(got, decoder.pack_planes_u64(decoder.masked_planes(enc)))
+    dense = decoder.dequantize_f32(enc)
+    buf32 = torch.full((m, n + pad), -3.0, dtype=torch.float32, device="cuda:0")
+    xe.decode(L, xe.OUT_F32, out=buf32[:, :n])
+    g32 = buf32.cpu().numpy()
+    assert np.array_equal(g32[:, :n].view(np.uint32), dense.view(np.uint32))
+    assert np.all(g32[:, n:] == -3.0)
+    buf16 = torch.full((m, n + pad), -3.0, dtype=torch.bfloat16, device="cuda:0")
+    xe.decode(L, xe.OUT_BF16, out=buf16[:, :n])
+    g16 = buf16.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(g16[:, :n], decoder.round_f32_to_bf16_bits(dense))
+    assert np.all(g16[:, n:] == 0xC040)          # bf16 pattern of -3.0: the padding is untouched
+
+
 def test_dense_output_with_leading_dimension_leaves_padding_untouched():
     import torch
     import paper_1905_10138_amd as xe

@@ -211,3 +211,29 @@ def test_output_leading_dimension_and_overwrite():
     got = buf.cpu().numpy()
     assert rel_fro(got[:, :64], decoder.spmm_f64(enc, exact)) <= TOL["bf16"]
     assert np.all(got[:, 64:] == 3.0)
+
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    names = ["tiny", "fig1", "fc6", "lstm", "large_q1", "large_q2"]
+    cases = []
+    for _ in range(count):
+        name = names[int(rng.integers(len(names)))]
+        n_out = int(rng.choice([64, 64, 64, 128, 192, 256]))
+        n_in = int(rng.integers(4, 33))
+        m = int(rng.integers(1, 300))
+        n = int(rng.integers(1, 1500))
+        B = int(rng.choice([1, 2, 3, 7, 8, 16, 24, 31, 32, 33, 40, 64, 65, 96, 128, 200, 256, 300]))
+        dtype = "f32" if rng.random() < 0.25 else "bf16"
+        pad = int(rng.choice([0, 0, 0, 1, 8]))
+        cases.append((name, m, n, n_out, n_in, B, dtype, pad))
+    return cases
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,B,dtype,pad", _random_cases(48, 20240611))
+def test_spmm_random_shapes(name, m, n, n_out, n_in, B, dtype, pad):
+    """Seeded random geometry: every slice width, any n_in, ragged m / n / B, padded leading dimension."""
+    got, want = _run(name, m, n, B, dtype, ldx_pad=pad, n_out=n_out, n_in=n_in)
+    assert got.shape == want.shape == (m, B)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL[dtype]
