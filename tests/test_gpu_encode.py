@@ -73,6 +73,26 @@ def test_gpu_exhaustive_encoder_matches_oracle(name, m, n, n_out, n_in, S):
     assert np.all(enc.n_patch <= alg1.n_patch)          # never worse than Algorithm 1, slice by slice
 
 
+def _random_encoder_cases(count, seed, max_n_in):
+    rng = np.random.default_rng(seed)
+    names = ["tiny", "fig1", "fc6", "lstm", "large_q1", "large_q2"]
+    return [(names[int(rng.integers(len(names)))], int(rng.integers(1, 200)), int(rng.integers(1, 1200)),
+             int(rng.choice([64, 64, 128, 192, 256])), int(rng.integers(4, max_n_in + 1)),
+             float(rng.choice([0.7, 0.85, 0.95]))) for _ in range(count)]
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,S", _random_encoder_cases(16, 5, 32))
+def test_gpu_encoder_random_geometries(name, m, n, n_out, n_in, S):
+    wl, enc = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in)
+    _check_against_oracle(wl, enc)
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,S", _random_encoder_cases(10, 6, 12))
+def test_gpu_exhaustive_encoder_random_geometries(name, m, n, n_out, n_in, S):
+    wl, enc = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in, exhaustive=True)
+    _check_against_oracle(wl, enc, exhaustive=True)
+
+
 def test_exhaustive_encoder_rejects_large_n_in():
     import torch
     import paper_1905_10138_amd as xe
