@@ -877,7 +877,8 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
   int ks = 1;
   const int base = row_groups * col_groups;
   const int max_ks = (D.spr + NW - 1) / NW;
-  if (base < 256) ks = max(1, min(max_ks, (256 + base - 1) / base));  // one workgroup per CU: a second round would pay prologue and epilogue again
+  // at most 256 workgroups: these variants run one per CU, and a second round would pay prologue and epilogue again
+  if (base < 256) ks = max(1, min(max_ks, 256 / base));
   int sps = (D.spr + ks - 1) / ks;
   sps = (sps + NW - 1) / NW * NW;
   ks = (D.spr + sps - 1) / sps;

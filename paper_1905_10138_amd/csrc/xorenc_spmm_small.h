@@ -356,7 +356,7 @@ inline bool small_plan(const DevLayer &D, int B, int RB, int *ks_out, int *sps_o
   const int row_groups = (D.nrb + RB - 1) / RB;
   int ks = 1;
   const int max_ks = (D.spr + NW - 1) / NW;
-  if (row_groups < 256) ks = max(1, min(max_ks, (256 + row_groups - 1) / row_groups));
+  if (row_groups < 256) ks = max(1, min(max_ks, 256 / row_groups));  // at most one workgroup per CU
   int sps = (D.spr + ks - 1) / ks;
   sps = (sps + NW - 1) / NW * NW;
   // shrink the range until X^T fits
