@@ -948,13 +948,14 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
       return launch_spmm<2, Q, 2, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     }
     if (blocks == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
-    // 128-row tiles halve the number of times X is re-read; used once they still fill the chip
-    // with enough tiles for two workgroups per CU, four waves each: the two share the CU's LDS, so one's
-    // prologue and epilogue no longer wait for the other's to finish
-    if (D.J == 1 && D.nib <= 2 && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
+    // 128-row tiles halve the number of times X is re-read; used once they still fill most of the chip.
+    // Up to 256 of them run as eight-wave workgroups, one per CU, in a single round; more run as
+    // four-wave workgroups, two per CU, which share the CU's LDS so that one's prologue and epilogue do
+    // not wait for the other's to finish.
+    const int64_t tiles128 = (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64);
+    if (D.J == 1 && D.nib <= 2 && tiles128 > 256)
       return launch_spmm<2, Q, 4, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
-    if (D.J == 1 && (int64_t)((D.nrb + 3) / 4) * ((B + 63) / 64) >= 512)
-      return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (D.J == 1 && tiles128 >= 200) return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
     if (blocks == 1 && x_fast) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
@@ -962,10 +963,10 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     if (!x_fast) return launch_spmm<2, Q, 1, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     // two slice buffers per wave leave no room for the tables of multi-word slices
     if (D.J > 1) return launch_spmm<2, Q, 1, false, 8, 1, 1, 4>(D, X, ldx, B, Y, ldy, x_fast, st);
-    // 64-row tiles once they fill the chip: X is re-read half as often; with enough of them, four-wave
-    // workgroups that run two per CU
+    // 64-row tiles once they fill most of the chip: X is re-read half as often; more than 256 of them run as
+    // four-wave workgroups, two per CU
     const int64_t tiles64 = (int64_t)((D.nrb + 1) / 2) * ((B + 63) / 64);
-    if (D.nib <= 2 && tiles64 >= 512) return launch_spmm<2, Q, 2, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (D.nib <= 2 && tiles64 > 256) return launch_spmm<2, Q, 2, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (tiles64 >= 200) return launch_spmm<2, Q, 2, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 3) {

@@ -93,11 +93,12 @@ def test_spmm_full_size_configs(name, B):
 @pytest.mark.parametrize("name,m,n,B,n_in,S", [
     ("large_q1", 16384, 256, 256, 8, None), ("large_q1", 16390, 200, 248, 8, None), ("large_q1", 12288, 320, 384, 16, None),
     ("large_q1", 12290, 256, 376, 24, None), ("large_q1", 16384, 192, 256, 8, 0.8),
-    ("large_q2", 16390, 200, 136, 16, None), ("large_q2", 12810, 320, 64, 8, None), ("large_q2", 8200, 256, 256, 24, 0.85)])
+    ("large_q2", 16390, 200, 136, 16, None), ("large_q2", 12810, 320, 64, 8, None), ("large_q2", 8200, 256, 256, 24, 0.85),
+    ("large_q1", 8192, 256, 256, 8, None), ("large_q1", 8200, 200, 328, 16, None), ("large_q2", 8200, 320, 136, 8, None)])
 def test_tall_matrix_many_columns(name, m, n, B, n_in, S):
     """Enough tiles to fill the chip once or twice: the launches with 128-row tiles (one plane) or 64-row tiles
-    (two planes), with four waves per workgroup and two workgroups per CU from 512 tiles on (n_in <= 16) and
-    eight waves otherwise.  Ragged rows, columns and batch; a short reduction (3 to 5 slices over 4 or 8 waves:
+    (two planes), with eight waves per workgroup up to 256 tiles and four waves, two workgroups per CU, above
+    (n_in <= 16).  Ragged rows, columns and batch; a short reduction (3 to 5 slices over 4 or 8 waves:
     some waves get none)."""
     got, want = _run(name, m, n, B, "bf16", S=S, n_in=n_in)
     assert np.isfinite(got).all()
