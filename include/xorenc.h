@@ -211,7 +211,7 @@ XORENC_API int32_t xorenc_pack_bits(int32_t m, int32_t n, int32_t n_out, const u
  *              must compare patch_off_out[q*n_units] (the true total) with patch_capacity after the
  *              stream has run, and retry with a larger buffer if it is larger.
  *   workspace  DEV  uint64[q*n_slots] + uint32[q*n_units] bytes, 8-byte aligned (scratch, contents undefined after)
- * Three kernels are enqueued on hip_stream; nothing synchronises.
+ * Five kernels are enqueued on hip_stream (slices, three for the offset scan, patch entries); nothing synchronises.
  */
 XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out, const uint32_t *M_rows,
                                  const uint64_t *mask, const uint64_t *planes, uint8_t *enc_out,

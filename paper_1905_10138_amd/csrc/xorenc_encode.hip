@@ -185,14 +185,65 @@ __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParam
   store_enc_unit(P.enc, (int64_t)p * P.n_eslots + eslot, P.n_in, xb, valid);
 }
 
-// exclusive scan of counts[0..n) into off[0..n], one workgroup
-__global__ __launch_bounds__(1024) void scan_counts_kernel(const uint32_t *counts, uint32_t *off, int n) {
+// Exclusive scan of counts[0..n) into off[0..n] in three launches and without extra memory.  A block
+// covers SCAN_BLOCK consecutive items, SCAN_PER per thread.
+//   1. scan_local_kernel: prefix inside each block.  The first item of a block would be 0: that slot of
+//      the NEXT block (off[n] for the last block) takes this block's total instead.
+//   2. scan_blocks_kernel: one workgroup turns the totals parked in those slots into block offsets,
+//      off[b * SCAN_BLOCK] = offset of block b, off[n] = grand total.
+//   3. scan_add_kernel: every other item of a block adds the block's offset.
+constexpr int SCAN_THREADS = 256, SCAN_PER = 16, SCAN_BLOCK = SCAN_THREADS * SCAN_PER;
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_local_kernel(const uint32_t *counts, uint32_t *off, int n) {
+  __shared__ uint32_t wsum[SCAN_THREADS / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t first = (int64_t)blockIdx.x * SCAN_BLOCK + (int64_t)tid * SCAN_PER;
+  uint32_t v[SCAN_PER];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int i = 0; i < SCAN_PER; ++i) {
+    v[i] = (first + i < n) ? counts[first + i] : 0u;
+    sum += v[i];
+  }
+  // inclusive scan of the thread sums over the wave, then over the block's waves
+  uint32_t incl = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)incl, o, 64);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < SCAN_THREADS / 64; ++w) {
+    if (w < wave) before += wsum[w];
+    total += wsum[w];
+  }
+  uint32_t run = before + incl - sum;  // exclusive prefix of this thread's first item inside the block
+#pragma unroll
+  for (int i = 0; i < SCAN_PER; ++i) {
+    if (first + i < n && !(tid == 0 && i == 0)) off[first + i] = run;
+    run += v[i];
+  }
+  if (tid == 0) {
+    const int64_t next = ((int64_t)blockIdx.x + 1) * SCAN_BLOCK;
+    off[next < n ? next : n] = total;
+  }
+}
+
+__global__ __launch_bounds__(1024) void scan_blocks_kernel(uint32_t *off, int n, int nblocks) {
   __shared__ uint32_t part[1024];
   const int tid = threadIdx.x;
-  const int per = (n + 1023) / 1024;
-  const int a = min(n, tid * per), e = min(n, a + per);
+  // block b's total sits in slot (b+1)*SCAN_BLOCK (or n); thread t owns blocks [a, e)
+  const int per = (nblocks + 1023) / 1024;
+  const int a = min(nblocks, tid * per), e = min(nblocks, a + per);
+  auto slot = [&](int b) {
+    const int64_t next = ((int64_t)b + 1) * SCAN_BLOCK;
+    return next < n ? next : (int64_t)n;
+  };
   uint32_t s = 0;
-  for (int i = a; i < e; ++i) s += counts[i];
+  for (int b = a; b < e; ++b) s += off[slot(b)];
   part[tid] = s;
   __syncthreads();
   for (int d = 1; d < 1024; d <<= 1) {
@@ -201,12 +252,24 @@ __global__ __launch_bounds__(1024) void scan_counts_kernel(const uint32_t *count
     part[tid] += v;
     __syncthreads();
   }
-  uint32_t run = part[tid] - s;  // exclusive prefix of this thread's chunk
-  for (int i = a; i < e; ++i) {
-    off[i] = run;
-    run += counts[i];
+  uint32_t run = part[tid] - s;  // offset of block a
+  for (int b = a; b < e; ++b) {
+    const uint32_t t = off[slot(b)];
+    run += t;
+    off[slot(b)] = run;  // = offset of block b+1, or the grand total in off[n]
   }
-  if (tid == 1023) off[n] = part[1023];
+  if (tid == 0) off[0] = 0u;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_add_kernel(uint32_t *off, int n) {
+  if (blockIdx.x == 0) return;  // block 0's offset is 0
+  const int tid = threadIdx.x;
+  const int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK;
+  const uint32_t add = off[base];
+  const int64_t first = base + (int64_t)tid * SCAN_PER;
+#pragma unroll
+  for (int i = 0; i < SCAN_PER; ++i)
+    if (first + i < n && !(tid == 0 && i == 0)) off[first + i] += add;
 }
 
 __global__ __launch_bounds__(ENC_THREADS) void emit_patches_kernel(const uint64_t *pbits, const uint32_t *off,
@@ -310,7 +373,10 @@ int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32
     for (int i = 0; i < XORENC_MAX_N_OUT; ++i) P.M_rows[i] = i < n_out ? M_rows[i] : 0u;
     hipLaunchKernelGGL(encode_slices_kernel, dim3(eblocks), dim3(ENC_THREADS), 0, st, P);
   }
-  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, counts, patch_off_out, (int)n_counts);
+  const int nscan = (int)((n_counts + SCAN_BLOCK - 1) / SCAN_BLOCK);
+  hipLaunchKernelGGL(scan_local_kernel, dim3(nscan), dim3(SCAN_THREADS), 0, st, counts, patch_off_out, (int)n_counts);
+  hipLaunchKernelGGL(scan_blocks_kernel, dim3(1), dim3(1024), 0, st, patch_off_out, (int)n_counts, nscan);
+  hipLaunchKernelGGL(scan_add_kernel, dim3(nscan), dim3(SCAN_THREADS), 0, st, patch_off_out, (int)n_counts);
   hipLaunchKernelGGL(emit_patches_kernel, dim3(blocks), dim3(ENC_THREADS), 0, st, pbits, patch_off_out, patch_out,
                      patch_capacity, total);
   return xorenc_internal_check_launch();
