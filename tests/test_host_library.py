@@ -171,3 +171,32 @@ def test_paper_format_stream_matches_oracle(name, m, n, n_out, n_in, S):
         xe.paper_import(enc.m, enc.n, enc.n_in, enc.q, stream[:len(stream) // 2], 7, enc.n_out)
     with pytest.raises(xe.XorencError):
         xe.paper_sizes(enc.m, enc.n, enc.n_in, enc.q, n_patch, 0, enc.n_out)
+
+
+def _random_host_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    names = ["tiny", "fig1", "fc6", "lstm", "large_q1", "large_q2"]
+    return [(names[int(rng.integers(len(names)))], int(rng.integers(1, 120)), int(rng.integers(1, 700)),
+             int(rng.choice([64, 128, 192, 256])), int(rng.integers(4, 33)), float(rng.choice([0.6, 0.8, 0.95])))
+            for _ in range(count)]
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,S", _random_host_cases(20, 11))
+def test_random_geometries_pack_unpack_export_import(name, m, n, n_out, n_in, S):
+    """Seeded random geometries through every host-side transformation: paper arrays -> packed layout -> paper
+    arrays -> bit stream -> paper arrays; the content checker accepts the packed layer; the stream's parts add
+    up to the oracle's accounting."""
+    from oracle import paper_format
+    wl, enc = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in)
+    w_c, keep, n_patch, d_patch, M_rows = paper_format_arrays(enc)
+    L = pack_encoded(enc)
+    assert xe.check_packed(L) == 0
+    w2, k2, np2, dp2 = xe.unpack(L)
+    assert np.array_equal(w2, w_c) and np.array_equal(k2, keep)
+    assert np.array_equal(np2, n_patch) and np.array_equal(dp2, d_patch)
+    blk = int(np.random.default_rng(m * n).integers(1, 2 * enc.l + 1))
+    stream = xe.paper_export(enc.m, enc.n, enc.n_in, enc.q, w2, np2, dp2, blk, enc.n_out)
+    want = paper_format.sizes(enc.n_in, enc.n_out, enc.n_patch, blk)
+    assert stream.size == (want.total_bits + 7) // 8
+    w3, np3, dp3 = xe.paper_import(enc.m, enc.n, enc.n_in, enc.q, stream, blk, enc.n_out)
+    assert np.array_equal(w3, w_c) and np.array_equal(np3, n_patch) and np.array_equal(dp3, d_patch)
