@@ -40,7 +40,7 @@ def test_planes_bit_exact(name, m, n):
     assert np.array_equal(want, decoder.pack_planes_u64(wl.planes))
 
 
-@pytest.mark.parametrize("name,m,n", SMALL + FULL[:1] + FULL[2:4])
+@pytest.mark.parametrize("name,m,n", SMALL + FULL)
 def test_dense_f32_and_bf16_bit_exact(name, m, n):
     import torch
     import paper_1905_10138_amd as xe
@@ -133,3 +133,22 @@ def test_unit_inputs_decode_to_columns_of_M():
                  np.ones((1, m), np.float32), gf2.bits_to_int(M).astype(np.uint32)).to(torch.device("cuda:0"))
     got2 = xe.decode(L2, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
     assert np.all(got2 == (cols[0] ^ cols[2]))
+
+
+def test_dense_decode_sums_three_planes_left_to_right():
+    """Scales (1, 2^-24, 2^-24) per row: (+-1 +- 2^-24) +- 2^-24 in fp32 depends on the order of the additions
+    (ties round to even), so only the left-to-right sum of the planes matches the oracle bit for bit."""
+    import copy
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc0 = encoded_workload("lstm", 130, 3000)
+    enc = copy.copy(enc0)
+    tiny = np.float32(2.0 ** -24)
+    enc.alpha = np.stack([np.ones(enc.m, np.float32), np.full(enc.m, tiny), np.full(enc.m, tiny)])
+    L = pack_encoded(enc).to(torch.device("cuda:0"))
+    want = decoder.dequantize_f32(enc)
+    got = xe.decode(L, xe.OUT_F32).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert np.abs(want).max() == np.float32(1.0)       # never 1 + 2^-23, which the other order would give
+    got16 = xe.decode(L, xe.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(want))

@@ -42,6 +42,29 @@ def test_hand_computed_decode():
     assert packed.tolist() == [[0b0001, 0b1110, 0b0001, 0b0101]]
 
 
+def test_dense_fp32_sums_planes_left_to_right():
+    """Three planes with scales (1, 2^-24, 2^-24), written by hand: in fp32, (1 + 2^-24) + 2^-24 is 1 (each
+    addition is a tie that rounds to the even neighbour 1.0) while 1 + (2^-24 + 2^-24) is 1 + 2^-23; with
+    signs (-, -, -) the mirror image.  Only the left-to-right order gives exactly +-1."""
+    M = np.array([[1, 0], [0, 1], [1, 1], [0, 0]], dtype=np.uint8)
+    w_c = np.array([[[1, 0]], [[1, 0]], [[1, 0]]], dtype=np.uint8)       # every plane decodes to 1,0,1,0
+    tiny = np.float32(2.0 ** -24)
+    alpha = np.array([[1.0], [tiny], [tiny]], dtype=np.float32)
+    enc = encoder.Encoded(m=1, n=4, n_pad=4, n_in=2, n_out=4, q=3, M=M, w_c=w_c,
+                          n_patch=np.zeros((3, 1), dtype=np.int32), d_patch=[np.zeros(0, dtype=np.int64)] * 3,
+                          keep=np.ones((1, 4), dtype=bool), alpha=alpha)
+    W = decoder.dequantize_f32(enc)
+    assert W.dtype == np.float32
+    assert W.tolist() == [[1.0, -1.0, 1.0, -1.0]]
+    right_to_left = np.float32(1.0) + (tiny + tiny)
+    assert right_to_left != np.float32(1.0)                               # the other order is visibly different
+    # the fp64 reference keeps all three terms
+    assert decoder.dequantize_f64(enc)[0, 0] == 1.0 + 2.0 ** -23
+    # a different order of the planes changes the fp32 result: (2^-24 + 2^-24) + 1 = 1 + 2^-23
+    enc.alpha = alpha[::-1].copy()
+    assert decoder.dequantize_f32(enc)[0, 0] == right_to_left
+
+
 def test_masked_planes_equal_quantised_bits_exactly():
     wl, enc = _encoded("lstm", 64, 200)
     assert np.array_equal(decoder.masked_planes(enc), wl.planes)
