@@ -9,14 +9,17 @@
 
 static thread_local int32_t g_last_hip_error = 0;
 
-int32_t xorenc_internal_check_launch(void) {
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    g_last_hip_error = (int32_t)e;
+int32_t xorenc_internal_hip_status(int32_t hip_error) {
+  if (hip_error != (int32_t)hipSuccess) {
+    g_last_hip_error = hip_error;
     return XORENC_EHIP;
   }
   return XORENC_OK;
 }
+
+int32_t xorenc_internal_check_launch(void) { return xorenc_internal_hip_status((int32_t)hipGetLastError()); }
+
+void xorenc_internal_begin_call(void) { (void)hipGetLastError(); }
 
 int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   if (!layer || layer->struct_size != sizeof(xorenc_layer)) return XORENC_EINVAL;
@@ -237,6 +240,7 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   if (out_kind != XORENC_OUT_PLANES && ld_out < layer->n) return XORENC_EINVAL;
   const uintptr_t al = out_kind == XORENC_OUT_PLANES ? 7 : (out_kind == XORENC_OUT_F32 ? 3 : 1);
   if ((uintptr_t)out & al) return XORENC_EALIGN;
+  xorenc_internal_begin_call();
   // at most a few thousand workgroups, each walking over several runs of 256 slots, so that the tables
   // are not built once per run
   const int64_t runs = (D.n_slots + 255) / 256;

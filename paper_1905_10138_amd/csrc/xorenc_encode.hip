@@ -310,6 +310,7 @@ int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32
   if (rc != XORENC_OK) return rc;
   if (!M_rows || !mask || !planes || !enc_out || !patch_off_out || !workspace || patch_capacity < 0)
     return XORENC_EINVAL;
+  xorenc_internal_begin_call();
   if (patch_capacity > 0 && !patch_out) return XORENC_EINVAL;
   if (exhaustive && n_in > XORENC_EXH_MAX_N_IN) return XORENC_EUNSUPPORTED;
   const int64_t total = (int64_t)q * sz.n_slots;

@@ -9,5 +9,10 @@
 
 /* hipGetLastError() -> XORENC_OK / XORENC_EHIP; remembers the hipError_t per thread. */
 int32_t xorenc_internal_check_launch(void);
+/* The same for the return value of a HIP call (a hipError_t passed as an integer). */
+int32_t xorenc_internal_hip_status(int32_t hip_error);
+/* First thing a GPU entry point does: drops an error that an earlier HIP call of the caller left behind in
+ * the runtime's per-thread slot, so that xorenc_internal_check_launch reports this call's launches only. */
+void xorenc_internal_begin_call(void);
 
 #endif

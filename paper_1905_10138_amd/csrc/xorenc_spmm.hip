@@ -21,6 +21,7 @@ extern "C" int32_t xorenc_spmm(const xorenc_layer *layer, const void *X, int32_t
   const bool enc_fast = (D.n_in & (D.n_in - 1)) == 0 || D.nib == 3;
   const int x_fast = (enc_fast && (B % per == 0) && (ldx % per == 0) && (((uintptr_t)X & 15) == 0)) ? 1 : 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  xorenc_internal_begin_call();
   switch (layer->q) {
     case 1: return xorenc_spmm_dispatch_q1(D, X, x_dtype, ldx, B, Y, ldy, x_fast, st);
     case 2: return xorenc_spmm_dispatch_q2(D, X, x_dtype, ldx, B, Y, ldy, x_fast, st);

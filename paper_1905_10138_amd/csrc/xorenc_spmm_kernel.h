@@ -112,7 +112,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
                               : (JT == 1)                ? 148 * 1024
                                                          : 160 * 1024 - 2048 - JT * NIBMAX * 2048;
   constexpr int FIT = TILE_BUDGET / (TILE * 4);
-  constexpr int NREG = largest_divisor_at_most(NW, FIT < 8 ? FIT : 8);
+  constexpr int NREG = largest_divisor_at_most(NW, FIT);
   constexpr int LDSB = (NW * XBUF > NREG * TILE * 4) ? NW * XBUF : NREG * TILE * 4;
   static_assert(!XF32 || NCB % 3 == 0, "fp32 X uses three bf16 terms per column");
   static_assert(FIT >= 1, "a reduction tile must fit in the X buffers");
@@ -807,12 +807,15 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
           for (int j4 = 0; j4 < 4; ++j4) {
-            // four consecutive rows of one column: one 16-byte LDS access
-            f32x4 *dst = reinterpret_cast<f32x4 *>(tile + (cb * 32 + rl) * TS + rb * 32 + 8 * j4 + 4 * g);
-            f32x4 v = {acc[0][rb][cb][4 * j4], acc[0][rb][cb][4 * j4 + 1], acc[0][rb][cb][4 * j4 + 2],
-                       acc[0][rb][cb][4 * j4 + 3]};
-            if (round != 0) v += *dst;
-            *dst = v;
+            // four consecutive rows of one column: one 16-byte LDS access; columns beyond B are never
+            // stored, so their lanes stay out (with few columns most of the tile is such padding)
+            if (XF32 || col0 + cb * 32 + rl < B) {
+              f32x4 *dst = reinterpret_cast<f32x4 *>(tile + (cb * 32 + rl) * TS + rb * 32 + 8 * j4 + 4 * g);
+              f32x4 v = {acc[0][rb][cb][4 * j4], acc[0][rb][cb][4 * j4 + 1], acc[0][rb][cb][4 * j4 + 2],
+                         acc[0][rb][cb][4 * j4 + 3]};
+              if (round != 0) v += *dst;
+              *dst = v;
+            }
           }
     }
     __syncthreads();
