@@ -36,7 +36,7 @@ extern "C" {
 #define XORENC_API
 #endif
 
-#define XORENC_VERSION 0x00020100u
+#define XORENC_VERSION 0x00020200u
 
 enum {
   XORENC_OK = 0,
@@ -44,7 +44,8 @@ enum {
   XORENC_EUNSUPPORTED = -2, /* n_out not in {64,128,192,256}, n_in not in 4..32, q not in 1..4, unknown dtype */
   XORENC_EALIGN = -3,       /* a device pointer or leading dimension breaks the stated alignment */
   XORENC_EHIP = -4,         /* a HIP runtime call failed; see xorenc_last_hip_error() */
-  XORENC_EFORMAT = -5       /* xorenc_pack / xorenc_check_packed found malformed content */
+  XORENC_EFORMAT = -5,      /* xorenc_pack / xorenc_check_packed found malformed content */
+  XORENC_ELIMIT = -6        /* the request needs more than a fixed capacity of the library (see the entry point) */
 };
 
 enum { XORENC_OUT_PLANES = 0, XORENC_OUT_F32 = 1, XORENC_OUT_BF16 = 2 };
@@ -232,6 +233,24 @@ XORENC_API int32_t xorenc_encode_exhaustive(int32_t m, int32_t n, int32_t n_in, 
                                             uint8_t *enc_out, uint32_t *patch_off_out, uint16_t *patch_out,
                                             int64_t patch_capacity, void *workspace, int64_t workspace_bytes,
                                             void *hip_stream);
+
+/*
+ * xorenc_encode for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs, kernels and
+ * stream behaviour as xorenc_encode, without the workspace: the patch bitmaps and the per-unit counts go to an
+ * area of XORENC_STATIC_SCRATCH_BYTES that the library keeps in device memory on every GPU it runs on, from
+ * the time it is loaded until the process ends.  Nothing is allocated or freed by this call (its first call on a
+ * device looks up the area's address once).  XORENC_ELIMIT if q*n_slots*8 + q*n_units*4 exceeds
+ * XORENC_STATIC_SCRATCH_BYTES (use xorenc_encode with a workspace of your own then).  Every call on a GPU
+ * uses that GPU's one area, whatever the stream: calls that overlap on one GPU race, the caller has to
+ * order them (one stream, or events).  The area needs no clearing between calls: every word a call reads it
+ * has written itself.
+ */
+#define XORENC_STATIC_SCRATCH_BYTES (24 * 1024 * 1024)
+XORENC_API int32_t xorenc_encode_static(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                        const uint32_t *M_rows, const uint64_t *mask, const uint64_t *planes,
+                                        uint8_t *enc_out, uint32_t *patch_off_out, uint16_t *patch_out,
+                                        int64_t patch_capacity, void *hip_stream);
 
 /*
  * Decode only (Sections 3.1-3.2 + mask + dequantisation).

@@ -5,12 +5,14 @@ from .binding import (
     OUT_BF16,
     OUT_F32,
     OUT_PLANES,
+    STATIC_SCRATCH_BYTES,
     PackedLayer,
     XorencError,
     check_packed,
     decode,
     encode,
     encode_exhaustive,
+    encode_static,
     get_sizes,
     library_path,
     load_library,
@@ -26,7 +28,7 @@ from .binding import (
 )
 
 __all__ = [
-    "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode", "encode", "encode_exhaustive",
+    "OUT_BF16", "OUT_F32", "OUT_PLANES", "PackedLayer", "XorencError", "check_packed", "decode", "encode", "encode_exhaustive", "encode_static", "STATIC_SCRATCH_BYTES",
     "pack_bits",
     "paper_export", "paper_import", "paper_sizes", "get_sizes", "library_path", "load_library", "pack", "spmm", "strerror", "unpack", "version",
 ]

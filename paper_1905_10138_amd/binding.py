@@ -83,6 +83,8 @@ def load_library():
     lib.xorenc_paper_import.argtypes = [i32, i32, i32, i32, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.xorenc_encode_exhaustive.restype = i32
     lib.xorenc_encode_exhaustive.argtypes = lib.xorenc_encode.argtypes
+    lib.xorenc_encode_static.restype = i32
+    lib.xorenc_encode_static.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.xorenc_decode.restype = i32
     lib.xorenc_decode.argtypes = [ctypes.POINTER(_Layer), i32, vp, i64, vp]
     lib.xorenc_spmm.restype = i32
@@ -306,6 +308,22 @@ def encode_exhaustive(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity
     """xorenc_encode_exhaustive on the current stream; arguments and result as `encode`."""
     return encode(m, n, n_in, q, M_rows, mask, planes, alpha, patch_capacity, n_out,
                   _entry="xorenc_encode_exhaustive")
+
+
+STATIC_SCRATCH_BYTES = 24 * 1024 * 1024
+
+
+def encode_static(m, n, n_in, q, M_rows, mask, planes, enc_out, patch_off_out, patch_out, n_out: int = 64) -> None:
+    """xorenc_encode_static on the current stream: like xorenc_encode, but the scratch memory is the library's
+    own static area, and every output buffer is the caller's (GPU tensors: enc_out uint8[enc_bytes],
+    patch_off_out int32[q*n_units + 1], patch_out int16[capacity]).  Nothing is allocated and nothing
+    synchronises; read patch_off_out[-1] afterwards to learn the patch total."""
+    M_rows = _as(M_rows, np.uint32).reshape(n_out)
+    _check(load_library().xorenc_encode_static(
+        m, n, n_in, q, n_out, _np_ptr(M_rows), ctypes.c_void_p(mask.data_ptr()), ctypes.c_void_p(planes.data_ptr()),
+        ctypes.c_void_p(enc_out.data_ptr()), ctypes.c_void_p(patch_off_out.data_ptr()),
+        ctypes.c_void_p(patch_out.data_ptr()) if patch_out.numel() else None, patch_out.numel(), _stream_ptr()),
+        "xorenc_encode_static")
 
 
 def check_packed(layer: PackedLayer) -> int:

@@ -16,11 +16,38 @@
 // the mismatches on its own slice.  Ties go to the smallest input read as an integer.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "xorenc_device.h"
+
+// Scratch area of xorenc_encode_static: device memory that every GPU holds from the time the library is loaded.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the looked-up address.
+static __device__ __align__(256) unsigned char scratch[XORENC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 constexpr int ENC_THREADS = 256;
+constexpr int kMaxDevices = 64;
+
+// Address of `scratch` on the current device, looked up once per device (with that device current).
+int32_t static_scratch_address(void **out) {
+  static std::mutex lock;
+  static void *address[kMaxDevices] = {};
+  int dev = -1;
+  const hipError_t ed = hipGetDevice(&dev);
+  if (ed != hipSuccess) return xorenc_internal_hip_status((int32_t)ed);
+  if (dev < 0 || dev >= kMaxDevices) return XORENC_EUNSUPPORTED;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!address[dev]) {
+    void *p = nullptr;
+    const hipError_t es = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (es != hipSuccess) return xorenc_internal_hip_status((int32_t)es);
+    if (!p) return XORENC_EHIP;
+    address[dev] = p;
+  }
+  *out = address[dev];
+  return XORENC_OK;
+}
 
 struct EncParams {
   const uint64_t *mask;
@@ -391,6 +418,22 @@ extern "C" int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, 
                                  void *workspace, int64_t workspace_bytes, void *hip_stream) {
   return encode_common(false, m, n, n_in, q, n_out, M_rows, mask, planes, enc_out, patch_off_out, patch_out,
                        patch_capacity, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int32_t xorenc_encode_static(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
+                                        const uint32_t *M_rows, const uint64_t *mask, const uint64_t *planes,
+                                        uint8_t *enc_out, uint32_t *patch_off_out, uint16_t *patch_out,
+                                        int64_t patch_capacity, void *hip_stream) {
+  xorenc_sizes sz;
+  const int32_t rc = xorenc_get_sizes(m, n, n_in, q, n_out, &sz);
+  if (rc != XORENC_OK) return rc;
+  const int64_t need = (int64_t)q * sz.n_slots * 8 + (int64_t)q * sz.n_units * 4;
+  if (need > (int64_t)XORENC_STATIC_SCRATCH_BYTES) return XORENC_ELIMIT;
+  void *area = nullptr;
+  const int32_t rs = static_scratch_address(&area);
+  if (rs != XORENC_OK) return rs;
+  return encode_common(false, m, n, n_in, q, n_out, M_rows, mask, planes, enc_out, patch_off_out, patch_out,
+                       patch_capacity, area, XORENC_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 extern "C" int32_t xorenc_encode_exhaustive(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,

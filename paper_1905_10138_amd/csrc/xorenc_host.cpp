@@ -18,6 +18,7 @@ const char *xorenc_strerror(int32_t code) {
     case XORENC_EALIGN: return "misaligned pointer or leading dimension";
     case XORENC_EHIP: return "HIP runtime call failed";
     case XORENC_EFORMAT: return "malformed compressed data";
+    case XORENC_ELIMIT: return "request exceeds a fixed capacity of the library (static scratch area)";
     default: return "unknown xorenc status";
   }
 }

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "xorenc.h")).read()
     names = set(re.findall(r"XORENC_API[^;(]*?\b(xorenc_\w+)\s*\(", text))
     assert {"xorenc_decode", "xorenc_spmm", "xorenc_pack", "xorenc_unpack", "xorenc_get_sizes",
-            "xorenc_encode", "xorenc_encode_exhaustive", "xorenc_paper_sizes", "xorenc_paper_export", "xorenc_paper_import",
+            "xorenc_encode", "xorenc_encode_exhaustive", "xorenc_encode_static", "xorenc_paper_sizes", "xorenc_paper_export", "xorenc_paper_import",
             "xorenc_check_packed", "xorenc_version", "xorenc_strerror",
             "xorenc_last_hip_error"} <= names
     for n in names:
