@@ -16,7 +16,8 @@
  *     pointers marked DEV are device memory owned by the caller, which must stay alive and
  *     unchanged until the work enqueued on `hip_stream` has run; inputs are never written;
  *   - GPU work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
- *     stream) of the current device; nothing synchronises and nothing allocates;
+ *     stream) of the current device; nothing synchronises and nothing allocates (scratch memory is either a
+ *     workspace argument or a fixed area inside the library, as each entry point says);
  *   - arguments are validated on the host before any GPU call; the *contents* of device
  *     buffers are not (use xorenc_check_packed on a host copy in tests).
  */
@@ -270,8 +271,13 @@ XORENC_API int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, vo
  *   Y  DEV float, row-major m x B, leading dimension ldy >= B; overwritten.
  * Accumulation is fp32; alpha is applied in fp32 after the contraction of each plane.  fp32 X is
  * split exactly into three bf16 terms, so the fp32 path keeps fp32 accuracy on the matrix cores.
- * When the launch splits the reduction dimension, partial sums meet in Y through fp32 atomics
- * after an internal zero-fill of Y on the same stream.
+ * One kernel launch per call, and the same bits in Y for the same inputs on every call: sums are formed in a
+ * fixed order.  For small layers the launch splits the reduction dimension over several workgroups per
+ * output tile; their partial tiles meet in a scratch area that the library keeps in device memory on every
+ * GPU (about 16 MiB, four slots taken in turn by successive calls), and the workgroup that finishes last adds
+ * them in the order of their slice ranges.  At most four such calls may therefore overlap on one GPU (on
+ * different streams; calls on one stream never overlap); a fifth could read another call's partial sums.
+ * Nothing is allocated by the call.
  */
 XORENC_API int32_t xorenc_spmm(const xorenc_layer *layer, const void *X, int32_t x_dtype, int64_t ldx, int32_t B, float *Y,
                     int64_t ldy, void *hip_stream);

@@ -32,6 +32,8 @@ int32_t xorenc_fill_dev_layer(const xorenc_layer *layer, DevLayer *D) {
   if (((uintptr_t)layer->mask & 7) || ((uintptr_t)layer->patch_off & 3) || ((uintptr_t)layer->alpha & 3) ||
       ((uintptr_t)layer->patch & 1) || ((uintptr_t)layer->enc & 3))
     return XORENC_EALIGN;
+  D->split_part = nullptr;
+  D->split_ticket = nullptr;
   D->enc = layer->enc;
   D->mask32 = reinterpret_cast<const uint32_t *>(layer->mask);
   D->patch_off = layer->patch_off;

@@ -20,11 +20,19 @@ struct DevLayer {
   int32_t n_in;
   int32_t J, espr;  // 64-bit words per slice (n_out/64), slices per row
   int64_t n_slots, n_eslots;
+  // Launches that split the reduction dimension over several workgroups per output tile: partial tiles
+  // (kSplitTileFloats floats per workgroup, at most kSplitMaxGroups workgroups) and one arrival counter per
+  // output tile, zero between launches.  Filled by xorenc_spmm from the library's own scratch area.
+  float *split_part;
+  uint32_t *split_ticket;
   // column j of M restricted to word w of a slice (rows 64 w .. 64 w + 63): lower and upper 32 rows
   uint32_t Mcol_lo[XORENC_MAX_J * XORENC_MAX_N_IN];
   uint32_t Mcol_hi[XORENC_MAX_J * XORENC_MAX_N_IN];
 };
 
+
+constexpr int kSplitTileFloats = 4096;  // largest output tile of a split launch (64 x 64)
+constexpr int kSplitMaxGroups = 256;    // workgroups of a split launch (one per CU)
 
 // T_{w,b}[v] for word w < J of a slice, b < nib, v < 256; entry ((w*nib + b)*256 + v) holds
 // {low 32 rows, high 32 rows} of the XOR of the columns 8b..8b+7 of M selected by the bits of v.

@@ -61,6 +61,27 @@ __device__ inline u32x4 expand_fp4_codes(uint32_t w) {
   return a;
 }
 
+// Partial sums of a split launch travel between workgroups that may sit on different XCDs, whose L2 caches are
+// not coherent with each other for ordinary accesses: relaxed device-scope atomic accesses go to the coherent
+// level directly, without the cache write-back and invalidation a fence would bring.
+__device__ inline void split_store(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float split_load(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// the same for 16 bytes at a time: buffer accesses with the sc0 and sc1 bits set (coherent at device scope)
+constexpr int kCoherentAux = 0x11;
+__device__ inline __amdgpu_buffer_rsrc_t split_rsrc(float *base) {
+  return __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7fffffff, 0x00020000u);
+}
+__device__ inline void split_store4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, kCoherentAux);
+}
+__device__ inline u32x4 split_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kCoherentAux);
+}
+
 constexpr int largest_divisor_at_most(int n, int cap) {
   int best = 1;
   for (int d = 1; d <= n && d <= cap; ++d)
@@ -81,7 +102,7 @@ struct BoolC {
 template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
 __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
-                                                      int use_atomic) {
+                                                      int n_splits) {
   constexpr int CW = 32 * NCB;                 // bf16 columns held in LDS per X row
   // XDIR: bf16 X with 16-byte aligned rows goes from global memory straight into LDS (no register
   // staging); the wave then owns two unpadded, swizzled slice buffers.  Otherwise X passes through
@@ -141,7 +162,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
   const int64_t l_n_eslots = (JT > 1) ? L.n_eslots : L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
                "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_nib), "s"(l_n_in), "s"(l_q), "s"(l_n_slots), "s"(Xv), "s"(ldx), "s"(B),
-               "s"(Y), "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
+               "s"(Y), "s"(ldy), "s"(slices_per_split), "s"(n_splits));
   // a wave that has not sent its first loads yet goes before the waves that already have
   __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x;
@@ -829,6 +850,13 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
     for (int r = 1; r < NREG; ++r) v += *reinterpret_cast<const f32x4 *>(src + r * TILE);
     return v;
   };
+  // n_splits > 1: this workgroup holds one of n_splits partial sums of its tile.  It parks the tile in the
+  // library's scratch area and takes a ticket; the workgroup that arrives last adds the parts in the order
+  // of their slice ranges (so the result does not depend on who was last) and writes Y.  No zero-fill, no
+  // atomics on Y, nobody waits for anybody.
+  float *const my_part =
+      n_splits > 1 ? L.split_part + ((int64_t)(blockIdx.y * gridDim.x + blockIdx.x) * n_splits + blockIdx.z) * kSplitTileFloats
+                   : nullptr;
   for (int idx = tid; idx < (ROWS / 4) * NR; idx += NW * 64) {
     const int rq = idx / NR, nn = idx % NR;
     const int gc = col0 + nn;
@@ -840,31 +868,52 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
       } else {
         v = reduced4(nn, rq);
       }
+      if (n_splits > 1) {
+        split_store4(split_rsrc(my_part), 16u * idx, __builtin_bit_cast(u32x4, v));
+      } else {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int gr = row0 + 4 * rq + k;
-        if (gr < l_m) {
-          float *dst = Y + (int64_t)gr * ldy + gc;
-          if (use_atomic)
-            unsafeAtomicAdd(dst, v[k]);
-          else
-            *dst = v[k];
+        for (int k = 0; k < 4; ++k) {
+          const int gr = row0 + 4 * rq + k;
+          if (gr < l_m) Y[(int64_t)gr * ldy + gc] = v[k];
         }
       }
     }
   }
-}
-
-static __global__ void zero_rows_kernel(float *Y, int64_t ldy, int m, int B) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < (int64_t)m * B) Y[(i / B) * ldy + (i % B)] = 0.f;
+  if (n_splits > 1) {
+    static_assert(ROWS * NR <= kSplitTileFloats || RB > 2, "a split launch's tile must fit its slot");
+    __shared__ uint32_t last_arrival;
+    const int tile_id = blockIdx.y * gridDim.x + blockIdx.x;
+    // the parts were written with device-coherent stores; once they are acknowledged the ticket may be taken
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) last_arrival = __hip_atomic_fetch_add(L.split_ticket + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(n_splits - 1) ? 1u : 0u;
+    __syncthreads();
+    if (last_arrival) {
+      const __amdgpu_buffer_rsrc_t parts = split_rsrc(L.split_part + (int64_t)tile_id * n_splits * kSplitTileFloats);
+      for (int idx = tid; idx < (ROWS / 4) * NR; idx += NW * 64) {
+        const int rq = idx / NR, nn = idx % NR;
+        const int gc = col0 + nn;
+        if (gc < B) {
+          f32x4 v = __builtin_bit_cast(f32x4, split_load4(parts, 16u * idx));
+          for (int z = 1; z < n_splits; ++z)
+            v += __builtin_bit_cast(f32x4, split_load4(parts, (uint32_t)z * (kSplitTileFloats * 4u) + 16u * idx));
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int gr = row0 + 4 * rq + k;
+            if (gr < l_m) Y[(int64_t)gr * ldy + gc] = v[k];
+          }
+        }
+      }
+      if (tid == 0) L.split_ticket[tile_id] = 0u;  // ready for the next launch
+    }
+  }
 }
 
 template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
 inline void launch_variant(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, dim3 grid,
-                           int sps, int atomic, hipStream_t st) {
+                           int sps, int n_splits, hipStream_t st) {
   hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, XFAST, PD, NIBT, JT>), grid, dim3(NW * 64), 0, st, D, X, ldx, B,
-                     Y, ldy, sps, atomic);
+                     Y, ldy, sps, n_splits);
 }
 
 // XMODE: 0 = the call site may see either layout, 1 = aligned X only, 2 = generic X only (keeps
@@ -881,18 +930,13 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
   const int base = row_groups * col_groups;
   const int max_ks = (D.spr + NW - 1) / NW;
   // at most 256 workgroups: these variants run one per CU, and a second round would pay prologue and epilogue again
-  if (base < 256) ks = max(1, min(max_ks, 256 / base));
+  if (base < kSplitMaxGroups && 32 * RB * NR <= kSplitTileFloats && D.split_part && D.split_ticket)
+    ks = max(1, min(min(max_ks, kSplitMaxGroups / base), 4));  // (the last workgroup of a tile reads every part)
   int sps = (D.spr + ks - 1) / ks;
   sps = (sps + NW - 1) / NW * NW;
   ks = (D.spr + sps - 1) / sps;
-  if (ks > 1) {
-    const int64_t tot = (int64_t)D.m * B;
-    hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, Y, ldy, D.m, B);
-    const int32_t rc = xorenc_internal_check_launch();
-    if (rc != XORENC_OK) return rc;
-  }
   const dim3 grid(row_groups, col_groups, ks);
-  const int atomic = ks > 1 ? 1 : 0;
+  const int atomic = ks;  // number of splits: the kernel reduces them through the scratch area when > 1
   // JMODE: 1 = slices of one 64-bit word only, 4 = up to four words (more table space), 0 = both
   if (D.J > 1 && JMODE == 1) return XORENC_EUNSUPPORTED;
   const bool wide = (JMODE == 4) || (JMODE == 0 && D.J > 1);

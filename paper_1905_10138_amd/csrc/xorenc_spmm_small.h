@@ -28,7 +28,7 @@ constexpr int kSmallXBytes = 96 * 1024;      // LDS set aside for X^T (rows padd
 template <int Q, int RB, int NW, int NIBT>
 __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const uint16_t *__restrict__ X, int64_t ldx,
                                                             int B, float *__restrict__ Y, int64_t ldy,
-                                                            int slices_per_split, int use_atomic) {
+                                                            int slices_per_split, int n_splits) {
   constexpr int ROWS = 32 * RB;
   constexpr int RED_FLOATS = NW * RB * kSmallMaxB * 32;  // partial results, over the X^T area after the loop
   static_assert(RED_FLOATS * 4 <= kSmallXBytes, "the reduction area must fit where X^T was");
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
   const int64_t l_n_slots = L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
                "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_q), "s"(n_in), "s"(l_n_slots), "s"(X), "s"(ldx), "s"(B), "s"(Y),
-               "s"(ldy), "s"(slices_per_split), "s"(use_atomic));
+               "s"(ldy), "s"(slices_per_split), "s"(n_splits));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -331,6 +331,10 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
     }
   }
   __syncthreads();
+  // n_splits > 1: the tile (ROWS x 8 floats) is one of n_splits partial sums; it is parked in the library's
+  // scratch area and the workgroup that arrives last adds the parts in the order of their slice ranges
+  float *const my_part =
+      n_splits > 1 ? L.split_part + ((int64_t)blockIdx.x * n_splits + blockIdx.z) * kSplitTileFloats : nullptr;
   for (int idx = tid; idx < ROWS * kSmallMaxB; idx += NW * 64) {
     const int r = idx >> 3, b = idx & 7;  // kSmallMaxB = 8 outputs per row
     const int gr = row0 + r;
@@ -339,11 +343,32 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
       float v = src[0];
 #pragma unroll
       for (int w = 1; w < NW; ++w) v += src[w * RB * kSmallMaxB * 32];
-      float *dst = Y + (int64_t)gr * ldy + b;
-      if (use_atomic)
-        unsafeAtomicAdd(dst, v);
+      if (n_splits > 1)
+        split_store(my_part + idx, v);
       else
-        *dst = v;
+        Y[(int64_t)gr * ldy + b] = v;
+    }
+  }
+  if (n_splits > 1) {
+    static_assert(ROWS * kSmallMaxB <= kSplitTileFloats, "the tile must fit its slot of the scratch area");
+    __shared__ uint32_t last_arrival;
+    // the parts were written with device-coherent stores; once they are acknowledged the ticket may be taken
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) last_arrival = __hip_atomic_fetch_add(L.split_ticket + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(n_splits - 1) ? 1u : 0u;
+    __syncthreads();
+    if (last_arrival) {
+      const float *parts = L.split_part + (int64_t)blockIdx.x * n_splits * kSplitTileFloats;
+      for (int idx = tid; idx < ROWS * kSmallMaxB; idx += NW * 64) {
+        const int r = idx >> 3, b = idx & 7;
+        const int gr = row0 + r;
+        if (b < B && gr < l_m) {
+          float v = split_load(parts + idx);
+          for (int z = 1; z < n_splits; ++z) v += split_load(parts + (int64_t)z * kSplitTileFloats + idx);
+          Y[(int64_t)gr * ldy + b] = v;
+        }
+      }
+      if (tid == 0) L.split_ticket[blockIdx.x] = 0u;  // ready for the next launch
     }
   }
 }
@@ -356,7 +381,8 @@ inline bool small_plan(const DevLayer &D, int B, int RB, int *ks_out, int *sps_o
   const int row_groups = (D.nrb + RB - 1) / RB;
   int ks = 1;
   const int max_ks = (D.spr + NW - 1) / NW;
-  if (row_groups < 256) ks = max(1, min(max_ks, 256 / row_groups));  // at most one workgroup per CU
+  if (row_groups < kSplitMaxGroups && D.split_part && D.split_ticket)
+    ks = max(1, min(max_ks, kSplitMaxGroups / row_groups));  // at most one workgroup per CU
   int sps = (D.spr + ks - 1) / ks;
   sps = (sps + NW - 1) / NW * NW;
   // shrink the range until X^T fits
@@ -371,14 +397,8 @@ inline bool small_plan(const DevLayer &D, int B, int RB, int *ks_out, int *sps_o
 template <int Q, int RB, int NW>
 int32_t launch_small(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, int ks, int sps,
                      hipStream_t st) {
-  if (ks > 1) {
-    const int64_t tot = (int64_t)D.m * B;
-    hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, Y, ldy, D.m, B);
-    const int32_t rc = xorenc_internal_check_launch();
-    if (rc != XORENC_OK) return rc;
-  }
   const dim3 grid((D.nrb + RB - 1) / RB, 1, ks);
-  const int atomic = ks > 1 ? 1 : 0;
+  const int atomic = ks;  // number of splits
   const uint16_t *Xh = static_cast<const uint16_t *>(X);
   switch (D.nib) {
     case 1:

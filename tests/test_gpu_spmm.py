@@ -247,3 +247,33 @@ def test_spmm_random_shapes(name, m, n, n_out, n_in, B, dtype, pad):
     assert got.shape == want.shape == (m, B)
     assert np.isfinite(got).all()
     assert rel_fro(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("name,m,n,B,dtype", [
+    ("fc6", 4096, 9216, 1, "bf16"), ("lstm", 6000, 3000, 1, "bf16"), ("fig1", 2048, 2048, 64, "bf16"),
+    ("lstm", 6000, 3000, 32, "bf16"), ("tiny", 256, 256, 8, "f32"), ("fc6", 97, 640, 3, "bf16")])
+def test_split_reduction_is_deterministic_and_one_launch(name, m, n, B, dtype):
+    """Layers with fewer output tiles than CUs split the reduction dimension over several workgroups per tile.
+    Their partial sums meet in the library's scratch area and are added in a fixed order: the same bits on
+    every call, also when calls on other layers come in between (the scratch slots are taken in turn and the
+    arrival counters must be back at zero after every launch), and Y needs no clearing beforehand."""
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc = encoded_workload(name, m, n)
+    L = pack_encoded(enc).to(torch.device("cuda:0"))
+    other_wl, other_enc = encoded_workload("fc6", 97, 640)
+    other = pack_encoded(other_enc).to(torch.device("cuda:0"))
+    stored, exact = draw_X(wl.n, B, dtype, wl.cfg.seed_X + 1000 * B)
+    xg = (torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16) if dtype == "bf16" else torch.from_numpy(stored)).to("cuda:0")
+    xo = torch.from_numpy(draw_X(other_wl.n, 5, "bf16", 3)[0].view(np.int16)).view(torch.bfloat16).to("cuda:0")
+    Y = torch.full((wl.m, B), float("nan"), dtype=torch.float32, device="cuda:0")   # stale content must not matter
+    xe.spmm(L, xg, Y=Y)
+    first = Y.clone()
+    assert rel_fro(first.cpu().numpy(), decoder.spmm_f64(enc, exact)) <= TOL[dtype]
+    assert_every_output_close(first.cpu().numpy(), decoder.spmm_f64(enc, exact), enc, exact) if dtype == "bf16" else None
+    for i in range(12):
+        if i % 3 == 1:
+            xe.spmm(other, xo)                  # another split launch in between: takes the next slot
+        Y.fill_(float(i))
+        xe.spmm(L, xg, Y=Y)
+        assert torch.equal(Y, first), f"call {i} differs"
