@@ -5,6 +5,8 @@
 // w = T_0[x & 255] ^ T_1[(x >> 8) & 255] ^ ...  where T_b[v] is the XOR of the columns 8b..8b+7 of
 // M selected by the bits of v: the same GF(2) product, eight columns at a time.  The tables are
 // rebuilt per workgroup from M, which travels in the kernel arguments.
+#include <algorithm>
+
 #include "xorenc_device.h"
 
 static thread_local int32_t g_last_hip_error = 0;
@@ -86,62 +88,149 @@ struct SlotStage {                       // phase-1 result of one slot, as phase
   float a[XORENC_MAX_Q];
 };
 
-__global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, void *out, int64_t ld, int chunks) {
-  extern __shared__ __attribute__((aligned(8))) uint32_t lut[];  // J * nib tables of 256 x 8 bytes (launch sizes it)
-  __shared__ __attribute__((aligned(8))) SlotStage stage[256];
+__global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, void *out, int64_t ld, int chunks,
+                                                     int groups_per_rb) {
+  // dynamic LDS (the launch sizes it): J * nib tables of 256 x 8 bytes, then the staging area of a run (dense
+  // output: 256 slots as phase 2 reads them; bit-planes: q x 8 x 33 words)
+  extern __shared__ __attribute__((aligned(16))) uint32_t lut[];
+  SlotStage *const stage = reinterpret_cast<SlotStage *>(lut + (size_t)L.J * L.nib * 512);
+  // Loads are requested ahead of their use: the words of a run that depend on nothing (mask, encrypted bits,
+  // patch range, scale) two runs ahead, the patch entries (whose address comes from the patch range) one run
+  // ahead; those of the first run go out before the tables are built.
+  struct RunWords {
+    uint64_t keep;
+    uint32_t xenc[XORENC_MAX_Q], pa[XORENC_MAX_Q], pe[XORENC_MAX_Q];
+    float a[XORENC_MAX_Q];
+  };
+  // Work decomposition: a workgroup takes `chunks` consecutive runs of one row block, a run = eight
+  // consecutive units (word positions 8k .. 8k+7), thread t = row t%32 of unit t/32 of the run.  Workgroups
+  // are numbered row block by row block, so neighbours touch neighbouring memory; the one division per
+  // workgroup replaces a division per slot.
+  const int rb = blockIdx.x / groups_per_rb, ky = blockIdx.x - rb * groups_per_rb;
+  const int rr = threadIdx.x & 31;
+  const int r = rb * 32 + rr;
+  auto word_of_slice = [&](int s, int &slice, int &wsel) {  // word s of a row is word s % J of slice s / J
+    switch (L.J) {                                           // uniform
+      case 1: slice = s; wsel = 0; break;
+      case 2: slice = s >> 1; wsel = s & 1; break;
+      case 4: slice = s >> 2; wsel = s & 3; break;
+      default: slice = s / 3; wsel = s - 3 * slice; break;
+    }
+  };
+  auto request = [&](int ch, RunWords &rw) {
+    const int s = (ky * chunks + ch) * 8 + (threadIdx.x >> 5);
+    const bool valid = ch < chunks && s < L.spr;
+    const int u = rb * L.spr + (valid ? s : 0);
+    const int64_t slot = (int64_t)u * 32 + rr;
+    rw.keep = valid ? ((uint64_t)L.mask32[2 * slot] | ((uint64_t)L.mask32[2 * slot + 1] << 32)) : 0ull;
+    int slice, wsel;
+    word_of_slice(valid ? s : 0, slice, wsel);
+    const int64_t eslot = ((int64_t)rb * L.espr + slice) * 32 + rr;
+#pragma unroll
+    for (int p = 0; p < XORENC_MAX_Q; ++p) {
+      rw.xenc[p] = rw.pa[p] = rw.pe[p] = 0u;
+      rw.a[p] = 0.f;
+      if (p < L.q && valid) {
+        rw.xenc[p] = load_enc(L.enc, (int64_t)p * L.n_eslots + eslot, L.n_in);
+        rw.pa[p] = L.patch_off[(int64_t)p * L.n_units + u];
+        rw.pe[p] = L.patch_off[(int64_t)p * L.n_units + u + 1];
+        if (out_kind != XORENC_OUT_PLANES && r < L.m) rw.a[p] = L.alpha[(int64_t)p * L.m + r];
+      }
+    }
+  };
+  // first 32 entries of the patch list of each plane: lane i of a unit fetches entry i
+  auto request_entries = [&](const RunWords &rw, uint32_t(&ent)[XORENC_MAX_Q]) {
+#pragma unroll
+    for (int p = 0; p < XORENC_MAX_Q; ++p) {
+      ent[p] = 0xFFFFu;  // row 1023: nobody's
+      if (p < L.q && (uint32_t)rr < rw.pe[p] - rw.pa[p]) ent[p] = (uint32_t)L.patch[rw.pa[p] + rr];
+    }
+  };
+  RunWords cur, nxt, nxt2;
+  uint32_t ent[XORENC_MAX_Q], ent_nxt[XORENC_MAX_Q];
+  request(0, cur);
+  request(1, nxt);
   build_xor_tables(lut, L);
   __syncthreads();
+  request_entries(cur, ent);
 
   const int lane = threadIdx.x & 63;
   for (int ch = 0; ch < chunks; ++ch) {
-    const int64_t chunk0 = ((int64_t)blockIdx.x * chunks + ch) * 256;
-    if (chunk0 >= L.n_slots) break;  // uniform
-    const int64_t slot = chunk0 + threadIdx.x;
-    const bool valid = slot < L.n_slots;
-    const int u = valid ? (int)(slot >> 5) : 0;  // n_units < 2^31 (checked on the host)
-    const int rr = (int)(slot & 31);
-    const int rb = u / L.spr, s = u % L.spr;
-    const int r = valid ? rb * 32 + rr : L.m;  // invalid lanes behave like a padding row
-    const uint64_t keep =
-        valid ? ((uint64_t)L.mask32[2 * slot] | ((uint64_t)L.mask32[2 * slot + 1] << 32)) : 0ull;
-
-    uint64_t w[XORENC_MAX_Q];
+    const int s0 = (ky * chunks + ch) * 8;  // first word position of the run
+    if (s0 >= L.spr) break;  // uniform
+    const int s = s0 + (threadIdx.x >> 5);
+    const bool valid = s < L.spr;
+    request(ch + 2, nxt2);
+    request_entries(nxt, ent_nxt);
+    const uint64_t keep = cur.keep;
+    int slice_unused, wsel;
+    word_of_slice(valid ? s : 0, slice_unused, wsel);
+    uint32_t xenc[XORENC_MAX_Q], pa[XORENC_MAX_Q], pe[XORENC_MAX_Q], mine32[XORENC_MAX_Q];
     float a[XORENC_MAX_Q];
 #pragma unroll
     for (int p = 0; p < XORENC_MAX_Q; ++p) {
+      xenc[p] = cur.xenc[p];
+      pa[p] = cur.pa[p];
+      pe[p] = cur.pe[p];
+      a[p] = cur.a[p];
+      mine32[p] = ent[p];
+      ent[p] = ent_nxt[p];
+    }
+    cur = nxt;
+    nxt = nxt2;
+    uint64_t w[XORENC_MAX_Q];
+#pragma unroll
+    for (int p = 0; p < XORENC_MAX_Q; ++p) {
       w[p] = 0;
-      a[p] = 0.f;
       if (p < L.q && valid) {
-        // word s of the row belongs to slice s / J and is word s % J of it
-        const int64_t eslot = ((int64_t)rb * L.espr + s / L.J) * 32 + rr;
-        const int wsel = s % L.J;
-        const uint32_t x = load_enc(L.enc, (int64_t)p * L.n_eslots + eslot, L.n_in);
         uint32_t lo = 0, hi = 0;
         for (int b = 0; b < L.nib; ++b) {
-          const int e = ((wsel * L.nib + b) << 8) + ((x >> (8 * b)) & 255);
+          const int e = ((wsel * L.nib + b) << 8) + ((xenc[p] >> (8 * b)) & 255);
           lo ^= lut[2 * e];
           hi ^= lut[2 * e + 1];
         }
-        uint64_t dec = (uint64_t)lo | ((uint64_t)hi << 32);
-        const uint32_t pa = L.patch_off[(int64_t)p * L.n_units + u];
-        const uint32_t pe = L.patch_off[(int64_t)p * L.n_units + u + 1];
-        for (uint32_t i = pa; i < pe; ++i) {
-          const uint32_t v = L.patch[i];
-          if ((int)(v >> 6) == rr) dec ^= 1ull << (v & 63);
-        }
-        w[p] = dec & keep;
-        if (out_kind != XORENC_OUT_PLANES && r < L.m) a[p] = L.alpha[(int64_t)p * L.m + r];
+        w[p] = (uint64_t)lo | ((uint64_t)hi << 32);
       }
+    }
+    // Patch flips.  The 32 lanes of a unit (half a wave) share one list: lane i fetches entry i (one round trip
+    // for the whole list instead of one per entry) and the entries are then passed round inside the unit.
+    // Every lane of the wave takes part in the exchange; lanes without a slot have an empty list.
+#pragma unroll
+    for (int p = 0; p < XORENC_MAX_Q; ++p) {
+      if (p >= L.q) break;  // uniform
+      const uint32_t cnt = pe[p] - pa[p];  // the same in all lanes of a unit
+      const uint32_t most = max(__shfl(cnt, 0, 64), __shfl(cnt, 32, 64));  // wave-uniform loop bound
+      for (uint32_t base = 0; base < most; base += 32) {
+        uint32_t mine = mine32[p];  // the first 32 entries were requested one run ago
+        if (base) mine = (base + (uint32_t)rr < cnt) ? (uint32_t)L.patch[pa[p] + base + rr] : 0xFFFFu;
+        const uint32_t here = min(32u, most - base);
+        for (uint32_t j = 0; j < here; ++j) {
+          const uint32_t v = (uint32_t)__shfl((int)mine, (int)j, 32);
+          if ((v >> 6) == (uint32_t)rr) w[p] ^= 1ull << (v & 63);
+        }
+      }
+      w[p] &= keep;
     }
 
     if (out_kind == XORENC_OUT_PLANES) {
-      if (r < L.m) {
+      // The slots of a run are 8 units x 32 rows; the output is row-major, so the words go through LDS and
+      // thread t writes word t%8 of row t/8: eight threads fill 64 consecutive bytes of a row (stride 33
+      // words per unit keeps the transposed reads on different banks).
+      uint64_t *park = reinterpret_cast<uint64_t *>(stage);
+#pragma unroll
+      for (int p = 0; p < XORENC_MAX_Q; ++p)
+        if (p < L.q) park[p * (8 * 33) + (threadIdx.x >> 5) * 33 + rr] = w[p];
+      __syncthreads();
+      const int un = threadIdx.x & 7, row = threadIdx.x >> 3;
+      const int s2 = s0 + un, r2 = rb * 32 + row;
+      if (s2 < L.spr && r2 < L.m) {
         uint64_t *o = static_cast<uint64_t *>(out);
         const int64_t l = (int64_t)L.m * L.spr;
 #pragma unroll
         for (int p = 0; p < XORENC_MAX_Q; ++p)
-          if (p < L.q) o[(int64_t)p * l + (int64_t)r * L.spr + s] = w[p];
+          if (p < L.q) o[(int64_t)p * l + (int64_t)r2 * L.spr + s2] = park[p * (8 * 33) + un * 33 + row];
       }
+      __syncthreads();  // the staging area is rewritten in the next run
       continue;
     }
 
@@ -165,11 +254,9 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
       for (int pass = 0; pass < 8 / EPL; ++pass) {
         const int idx = 64 * pass + lane;
         const int un = idx / G, g = idx % G;
-        const int64_t ul = (chunk0 >> 5) + un;  // this lane's unit (runs start at a multiple of 8 units)
-        const bool unit_ok = ul < (int64_t)L.n_units;
-        const int uj = unit_ok ? (int)ul : 0;
-        const int row_base = (uj / L.spr) * 32;
-        const int col = (uj % L.spr) * 64 + EPL * g;
+        const bool unit_ok = s0 + un < L.spr;  // this lane's unit of the run
+        const int row_base = rb * 32;
+        const int col = (s0 + un) * 64 + EPL * g;
         const int byte = (EPL * g) >> 3, shift = (EPL * g) & 7;
         for (int i = 0; i < 8; ++i) {
           const int row = 8 * (threadIdx.x >> 6) + i;
@@ -243,15 +330,19 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   const uintptr_t al = out_kind == XORENC_OUT_PLANES ? 7 : (out_kind == XORENC_OUT_F32 ? 3 : 1);
   if ((uintptr_t)out & al) return XORENC_EALIGN;
   xorenc_internal_begin_call();
-  // at most a few thousand workgroups, each walking over several runs of 256 slots, so that the tables
-  // are not built once per run
-  const int64_t runs = (D.n_slots + 255) / 256;
-  const int64_t wgs = out_kind == XORENC_OUT_F32 ? 4096 : 2048;  // measured: fp32 stores like more of them in flight
-  const int chunks = (int)((runs + wgs - 1) / wgs);
-  const unsigned blocks = (unsigned)((runs + chunks - 1) / chunks);
-  const size_t lut_bytes = (size_t)D.J * D.nib * 2048;  // small tables leave LDS for eight workgroups per CU
-  hipLaunchKernelGGL(decode_kernel, dim3(blocks), dim3(256), lut_bytes, static_cast<hipStream_t>(hip_stream), D,
-                     out_kind, out, ld_out, chunks);
+  // A workgroup takes `chunks` runs of eight word positions of one row block: a couple of thousand workgroups
+  // in all, so that all of them are resident at once and the tables are not built once per run.
+  const int64_t rpb = (D.spr + 7) / 8;  // runs per row block
+  const int64_t runs = rpb * D.nrb;
+  const int64_t wgs = out_kind == XORENC_OUT_F32 ? 4096 : (out_kind == XORENC_OUT_PLANES ? 1024 : 2048);  // measured: fp32 stores like more of them in flight
+  const int chunks = (int)std::min<int64_t>(rpb, (runs + wgs - 1) / wgs);
+  const int64_t groups_per_rb = (rpb + chunks - 1) / chunks;
+  if (groups_per_rb * D.nrb > 0x7fffffff) return XORENC_EUNSUPPORTED;
+  // tables (small ones leave LDS for eight workgroups per CU) + the staging area of a run
+  const size_t lds_bytes = (size_t)D.J * D.nib * 2048 +
+                           (out_kind == XORENC_OUT_PLANES ? (size_t)D.q * 8 * 33 * 8 : 256 * sizeof(SlotStage));
+  hipLaunchKernelGGL(decode_kernel, dim3((unsigned)(groups_per_rb * D.nrb)), dim3(256), lds_bytes,
+                     static_cast<hipStream_t>(hip_stream), D, out_kind, out, ld_out, chunks, (int)groups_per_rb);
   return xorenc_internal_check_launch();
 }
 
