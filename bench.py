@@ -9,12 +9,17 @@ round-robin over R replicas of the compressed layer, X and Y with R * bytes >= 1
 issued back to back on one stream from a captured HIP graph so that host launch cost does not
 pace the GPU.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.  Headline (`value`, `roofline`): the large one-bit matrix at B = 64.  `sweep`: the other
+batch sizes of that matrix.  `configs`: every configuration of the benchmark contract at each of its batch sizes,
+with its own roofline object.  `marginal`: the same recipe four times as tall, to separate what a launch costs
+from what a row of W costs.  `decode`, `fig1`, `n_out_192*`, `storage`, `encoder`: see the functions below.
 """
 import argparse
 import ctypes
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,6 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+LAUNCH_BOUND_US = 4.0           # below about this many microseconds of roofline time a kernel is mostly fixed cost
 
 
 def parse_args():
@@ -41,11 +47,12 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of W in the CPU-oracle sample (0 = auto)")
     ap.add_argument("--replica-bytes", type=float, default=float(1 << 30))
-    ap.add_argument("--decode-only", action="store_true", help="also time xorenc_decode (planes) on the workload")
     ap.add_argument("--no-wide", action="store_true", help="skip the n_out=192 / n_in=24 extra on the same matrix")
     ap.add_argument("--no-decode", action="store_true", help="skip the timing of xorenc_decode on the workload")
     ap.add_argument("--no-encoder", action="store_true", help="skip the timing of the two GPU encoders")
     ap.add_argument("--no-fig1", action="store_true", help="skip the Fig. 1-shaped extra (decode-only and fused, B=64)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table")
+    ap.add_argument("--no-marginal", action="store_true", help="skip the four-times-taller matrix")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region run one 256 MiB device copy (reference dispatch for rocprofv3 --pmc)")
     return ap.parse_args()
@@ -73,66 +80,82 @@ def clone_layer(L, xe):
                           L.patch.clone(), L.alpha.clone(), L.n_out)
 
 
-class SpmmRunner:
-    """Pre-marshalled xorenc_spmm calls over R replicas (no Python work per step beyond the ctypes call)."""
+def tile_rows(L, times, xe, torch):
+    """The layer repeated `times` times downwards (m a multiple of 32): pure re-arrangement of the packed
+    buffers on the GPU.  Gives a taller matrix of the same recipe without encoding one."""
+    assert L.m % 32 == 0
+    q = L.q
+    U = (L.patch_off.numel() - 1) // q                       # units per plane
+    off = L.patch_off.to(torch.int64)
+    enc = L.enc.view(q, -1).repeat(1, times).reshape(-1)
+    mask = L.mask.repeat(times)
+    alpha = L.alpha.repeat(1, times)
+    new_off, new_patch, base = [], [], 0
+    for p in range(q):
+        lo, hi = int(off[p * U]), int(off[(p + 1) * U])
+        rel = off[p * U:(p + 1) * U] - lo
+        for _ in range(times):
+            new_off.append(rel + base)
+            new_patch.append(L.patch[lo:hi])
+            base += hi - lo
+    new_off.append(torch.tensor([base], dtype=torch.int64, device=off.device))
+    patch_off = torch.cat(new_off).to(torch.int32)
+    patch = torch.cat(new_patch) if base else L.patch[:0]
+    return xe.PackedLayer(L.m * times, L.n, L.n_in, q, L.M_rows, enc.contiguous(), mask.contiguous(), patch_off,
+                          patch.contiguous(), alpha.contiguous(), L.n_out)
 
-    def __init__(self, xe, torch, layer, x_dev, B, replica_bytes):
-        self.torch = torch
-        self.lib = xe.load_library()
-        self.B = B
-        xbytes = x_dev.numel() * x_dev.element_size()
-        ybytes = layer.m * B * 4
-        self.comp_bytes = layer.compressed_bytes()
-        self.step_bytes = self.comp_bytes + xbytes + ybytes
-        R = int(min(256, max(2, np.ceil(replica_bytes / self.step_bytes))))
-        self.layers = [layer] + [clone_layer(layer, xe) for _ in range(R - 1)]
-        self.xs = [x_dev] + [x_dev.clone() for _ in range(R - 1)]
-        self.ys = [torch.empty((layer.m, B), dtype=torch.float32, device=x_dev.device) for _ in range(R)]
-        self.structs = [l.c_struct() for l in self.layers]
-        xd = 0 if x_dev.dtype == torch.float32 else 1
-        self.calls = []
-        for st, x, y in zip(self.structs, self.xs, self.ys):
-            self.calls.append((ctypes.byref(st), ctypes.c_void_p(x.data_ptr()), xd, x.stride(0), B,
-                               ctypes.c_void_p(y.data_ptr()), y.stride(0)))
-        self.R = R
+
+class GraphRunner:
+    """Pre-marshalled C-ABI calls over R replicas, issued from a captured HIP graph of min(R, steps) calls
+    (so that a replay happens even for few steps) plus an eager remainder.  No Python work per call beyond
+    the ctypes call itself."""
+
+    def __init__(self, torch, fn, calls, what):
+        self.torch, self.fn, self.calls, self.what = torch, fn, calls, what
+        self.R = len(calls)
         self.pos = 0
         self.graph = None
+        self.graph_len = 0
+        self.replays = 0
 
     def launch(self, count):
-        fn = self.lib.xorenc_spmm
         stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
         for _ in range(count):
-            rc = fn(*self.calls[self.pos], stream)
+            rc = self.fn(*self.calls[self.pos], stream)
             if rc != 0:
-                raise RuntimeError(f"xorenc_spmm failed with status {rc}")
+                raise RuntimeError(f"{self.what} failed with status {rc}")
             self.pos = (self.pos + 1) % self.R
 
-    def capture(self):
-        """Capture one rotation (R steps) into a HIP graph."""
+    def capture(self, steps):
         torch = self.torch
+        self.graph_len = max(1, min(self.R, steps))
         self.pos = 0
-        g = torch.cuda.CUDAGraph()
         s = torch.cuda.Stream()
         s.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(s):
             self.launch(self.R)  # warm the code objects before capture
         torch.cuda.current_stream().wait_stream(s)
         torch.cuda.synchronize()
+        self.pos = 0
+        g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            self.launch(self.R)
+            self.launch(self.graph_len)
         self.graph = g
 
-    def run(self, steps):
-        """Issue exactly `steps` steps (graph replays of R steps + an eager remainder)."""
+    def run(self, steps, count_replays=False):
         if self.graph is not None:
-            for _ in range(steps // self.R):
+            n = steps // self.graph_len
+            for _ in range(n):
                 self.graph.replay()
+            if count_replays:
+                self.replays += n
             self.pos = 0
-            self.launch(steps % self.R)
+            self.launch(steps % self.graph_len)
         else:
             self.launch(steps)
 
     def time(self, steps, warmup):
+        """(wall seconds, HIP-event seconds) of exactly `steps` calls on the current stream."""
         torch = self.torch
         self.run(warmup)
         torch.cuda.synchronize()
@@ -140,33 +163,120 @@ class SpmmRunner:
         e1 = torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         e0.record()
-        self.run(steps)
+        self.run(steps, count_replays=True)
         e1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         return wall, e0.elapsed_time(e1) * 1e-3
 
 
-def roofline_entry(flops, comp_bytes, total_bytes, sec_per_launch, B):
+def replica_count(replica_bytes, step_bytes):
+    return int(min(256, max(2, np.ceil(replica_bytes / step_bytes))))
+
+
+def spmm_runner(xe, torch, layer, x_dev, B, replica_bytes):
+    lib = xe.load_library()
+    xbytes = x_dev.numel() * x_dev.element_size()
+    comp = layer.compressed_bytes()
+    step_bytes = comp + xbytes + layer.m * B * 4
+    R = replica_count(replica_bytes, step_bytes)
+    layers = [layer] + [clone_layer(layer, xe) for _ in range(R - 1)]
+    xs = [x_dev] + [x_dev.clone() for _ in range(R - 1)]
+    ys = [torch.empty((layer.m, B), dtype=torch.float32, device=x_dev.device) for _ in range(R)]
+    structs = [l.c_struct() for l in layers]
+    xd = 0 if x_dev.dtype == torch.float32 else 1
+    calls = [(ctypes.byref(st), ctypes.c_void_p(x.data_ptr()), xd, x.stride(0), B, ctypes.c_void_p(y.data_ptr()), y.stride(0))
+             for st, x, y in zip(structs, xs, ys)]
+    runner = GraphRunner(torch, lib.xorenc_spmm, calls, "xorenc_spmm")
+    runner.keep = (layers, xs, ys, structs)  # the buffers live as long as the runner
+    runner.ys, runner.comp_bytes, runner.step_bytes = ys, comp, step_bytes
+    return runner
+
+
+def decode_runner(xe, torch, layer, kind, replica_bytes):
+    lib = xe.load_library()
+    out0 = xe.decode(layer, kind)
+    out_bytes = out0.numel() * out0.element_size()
+    R = min(64, replica_count(replica_bytes, layer.compressed_bytes() + out_bytes))
+    layers = [layer] + [clone_layer(layer, xe) for _ in range(R - 1)]
+    outs = [out0] + [torch.empty_like(out0) for _ in range(R - 1)]
+    structs = [l.c_struct() for l in layers]
+    ld = out0.stride(0) if kind != xe.OUT_PLANES else 0
+    calls = [(ctypes.byref(st), kind, ctypes.c_void_p(o.data_ptr()), ld) for st, o in zip(structs, outs)]
+    runner = GraphRunner(torch, lib.xorenc_decode, calls, "xorenc_decode")
+    runner.keep = (layers, outs, structs)
+    runner.bytes = layer.compressed_bytes() + out_bytes
+    return runner
+
+
+def kernel_source_digest():
+    """Digest of the kernel sources: a traffic profile applies only to the sources it was taken with."""
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_1905_10138_amd", "csrc")
+    for name in ("xorenc_spmm_kernel.h", "xorenc_spmm_small.h", "xorenc_spmm.hip", "xorenc_device.h"):
+        with open(os.path.join(src, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_from_profile(workload, B):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (FETCH_SIZE and
+    WRITE_SIZE, scaled by what the same counters read for a copy of known size), or None when there is no
+    summary, no row for this B, or the summary was taken with other kernel sources."""
+    path = os.path.join(ROOT, "profiles", f"spmm_{workload}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m = re.search(r"kernel sources digest: ([0-9a-f]+)", text)
+    if not m or m.group(1) != kernel_source_digest():
+        return None
+    for line in text.splitlines():
+        r = re.match(r"\|[^|]*\(B=(\d+)\)\s*\|\s*[\d.]+\s*\|\s*([\d.]+)\s*\|\s*[\d.]+\s*\|\s*([\d.]+)\s*\|", line)
+        if r and int(r.group(1)) == B:
+            return {"read_bytes": float(r.group(2)) * 1e6, "write_bytes": float(r.group(3)) * 1e6,
+                    "source": os.path.relpath(path, ROOT)}
+    return None
+
+
+def roofline_entry(flops, comp_bytes, total_bytes, sec_per_launch, B, workload=None):
     if B >= 32:
         ach = flops / sec_per_launch / 1e12
-        return {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
-    ach = comp_bytes / sec_per_launch / 1e9
-    return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-            "traffic": None, "total_bytes_gbs": total_bytes / sec_per_launch / 1e9}
+        ent = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+               "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        ideal_us = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
+    else:
+        ach = comp_bytes / sec_per_launch / 1e9
+        ent = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+               "traffic": None, "total_bytes_gbs": total_bytes / sec_per_launch / 1e9}
+        ideal_us = comp_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+    ent["roofline_us"] = ideal_us
+    ent["launch_bound"] = bool(ideal_us < LAUNCH_BOUND_US)   # the roofline time is below what any launch costs here
+    tr = traffic_from_profile(workload, B) if workload else None
+    if tr is not None:
+        ent["traffic"] = tr["read_bytes"] + tr["write_bytes"]
+        ent["traffic_read_bytes"], ent["traffic_write_bytes"], ent["traffic_source"] = tr["read_bytes"], tr["write_bytes"], tr["source"]
+    return ent
 
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), scaled by
-# what the same counters read for a 256 MiB device copy in the same run; see profiles/.
-# Filled in from the committed profile of this exact command; None = not measured.
-MEASURED_TRAFFIC = {
-    # profiles/spmm_large_q1_hbm_traffic.md: bytes read + written per launch
-    "large_q1:B1": {"read_bytes": 9.98e6, "write_bytes": 0.07e6},
-    "large_q1:B8": {"read_bytes": 10.48e6, "write_bytes": 0.52e6},
-    "large_q1:B64": {"read_bytes": 14.16e6, "write_bytes": 4.19e6},
-    "large_q1:B256": {"read_bytes": 26.75e6, "write_bytes": 16.78e6},
-}
+def x_tensor(torch, wl, B, dev):
+    stored, exact = wl.X(B)
+    if wl.cfg.x_dtype == "bf16":
+        return torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev), exact
+    return torch.from_numpy(stored).to(dev), exact
+
+
+def measure_spmm(xe, torch, layer, xg, B, m, n, args, steps, warmup, workload=None):
+    runner = spmm_runner(xe, torch, layer, xg, B, args.replica_bytes)
+    if not args.no_graph:
+        runner.capture(steps)
+    wall, ev = runner.time(steps, warmup)
+    flops = 2.0 * m * n * B
+    res = {"B": B, "ms_per_step": wall * 1e3 / steps, "us_per_launch_events": ev * 1e6 / steps,
+           "tflops": flops * steps / wall / 1e12, "compressed_gbs": runner.comp_bytes * steps / wall / 1e9,
+           "replicas": runner.R, "graph_replays": runner.replays, "step_bytes": runner.step_bytes,
+           "compressed_bytes": runner.comp_bytes,
+           "roofline": roofline_entry(flops, runner.comp_bytes, runner.step_bytes, ev / steps, B, workload)}
+    return res, runner
 
 
 def cpu_baseline(wl, B, x_exact, y_gpu_rows, rows):
@@ -193,56 +303,80 @@ def cpu_baseline(wl, B, x_exact, y_gpu_rows, rows):
             "seconds": t, "gpu_vs_oracle_rel_fro": err}
 
 
-def fig1_extra(xe, torch, dev, args):
-    """The Fig. 1-shaped configuration: decode-only (planes and dense bf16) and the fused product at B = 64."""
-    from synth_inputs import CONFIGS, make_workload
-    cfg = CONFIGS["fig1"]
-    wl = make_workload(cfg)
-    layer = build_layer(wl, xe, torch, dev)
-    stored, _ = wl.X(64)
-    xg = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev)
-    runner = SpmmRunner(xe, torch, layer, xg, 64, args.replica_bytes)
-    if not args.no_graph:
-        runner.capture()
-    steps = max(200, args.sweep_steps)
-    wall, ev = runner.time(steps, 50)
-    res = {"workload": f"fig1: W {cfg.m}x{cfg.n} S={cfg.S} q=1 n_in=16, X {cfg.n}x64 bf16",
-           "fused_us_per_launch": ev * 1e6 / steps, "fused_tflops": 2.0 * cfg.m * cfg.n * 64 * steps / wall / 1e12,
-           "compressed_bytes": runner.comp_bytes, "replicas": runner.R}
-    for kind, name, width in ((xe.OUT_PLANES, "decode_planes", 8 * ((cfg.n + 63) // 64) / cfg.n),
-                              (xe.OUT_BF16, "decode_bf16", 2.0)):
-        out = xe.decode(layer, kind)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(200):
-            xe.decode(layer, kind, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / 200
-        res[name + "_us"] = us
-        res[name + "_gbs"] = (layer.compressed_bytes() + cfg.m * cfg.n * width) / (us * 1e-6) / 1e9
+def decode_times(xe, torch, layer, args, kinds=None, steps=200):
+    """xorenc_decode on a layer: bit-planes, dense bf16 and dense fp32, over cold replicas from a HIP graph.
+    Bytes = compressed bytes read + output bytes written; the fraction is against 8 TB/s."""
+    res = {}
+    for kind, name in kinds or ((xe.OUT_PLANES, "planes"), (xe.OUT_BF16, "bf16"), (xe.OUT_F32, "f32")):
+        runner = decode_runner(xe, torch, layer, kind, args.replica_bytes)
+        if not args.no_graph:
+            runner.capture(steps)
+        wall, ev = runner.time(steps, 20)
+        us = ev * 1e6 / steps
+        res[name] = {"us": us, "bytes": runner.bytes, "gbs": runner.bytes / (us * 1e-6) / 1e9,
+                     "hbm_frac": runner.bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "replicas": runner.R}
+        del runner
     return res
 
 
-def decode_extra(xe, torch, layer, reps=50):
-    """xorenc_decode on the main workload's layer: bit-planes, dense bf16 and dense fp32.  Bytes = compressed
-    bytes read + output bytes written; the fraction is against 8 TB/s."""
-    res = {}
-    for kind, name in ((xe.OUT_PLANES, "planes"), (xe.OUT_BF16, "bf16"), (xe.OUT_F32, "f32")):
-        out = xe.decode(layer, kind)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            xe.decode(layer, kind, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        nbytes = layer.compressed_bytes() + out.numel() * out.element_size()
-        res[name] = {"us": us, "bytes": nbytes, "gbs": nbytes / (us * 1e-6) / 1e9,
-                     "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
-        del out
+def config_table(xe, torch, dev, args, done):
+    """Every configuration of the benchmark contract at each of its batch sizes (the headline matrix's
+    entries are the ones already measured).  Per entry: microseconds per launch, dense-equivalent TFLOP/s,
+    GB/s on the compressed bytes, and the roofline object of its bound."""
+    from synth_inputs import CONFIGS, make_workload
+    table = {}
+    for name, cfg in CONFIGS.items():
+        if name in done:
+            table[name] = done[name]
+            continue
+        wl = make_workload(cfg)
+        layer = build_layer(wl, xe, torch, dev)
+        weights = float(cfg.m) * cfg.n
+        ent = {"workload": f"W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in={cfg.n_in} n_out={cfg.n_out}, X {cfg.x_dtype}",
+               "compressed_bytes": layer.compressed_bytes(), "patches": int(layer.patch.numel()),
+               "patches_per_slice": float(layer.patch.numel()) / (cfg.q * cfg.m * -(-cfg.n // cfg.n_out)),
+               "stored_bits_per_weight": 8.0 * layer.compressed_bytes() / weights,
+               "encrypted_bits_per_weight": 8.0 * layer.enc.numel() / weights, "batches": {}}
+        for B in cfg.batches:
+            xg, _ = x_tensor(torch, wl, B, dev)
+            steps = max(100, args.sweep_steps // 2)
+            r, runner = measure_spmm(xe, torch, layer, xg, B, cfg.m, cfg.n, args, steps, 20, workload=name)
+            ent["batches"][f"B{B}"] = {k: r[k] for k in ("us_per_launch_events", "tflops", "compressed_gbs", "replicas",
+                                                        "graph_replays", "roofline")}
+            del runner
+        if name == "fig1":      # this configuration asks for decode-only next to the fused product
+            ent["decode"] = decode_times(xe, torch, layer, args, ((xe.OUT_PLANES, "planes"), (xe.OUT_BF16, "bf16")))
+        table[name] = ent
+        del layer
+        torch.cuda.empty_cache()
+    return table
+
+
+def marginal_rates(xe, torch, dev, args, wl, layer, base):
+    """The headline matrix repeated four times downwards (65536 x 4096, same recipe): time per launch at both
+    heights gives the cost of a row of W without the fixed cost of a launch: the slope, as TFLOP/s and GB/s of
+    compressed bytes, with the roofline fraction of each."""
+    tall = tile_rows(layer, 4, xe, torch)
+    res = {"workload": f"{wl.cfg.name} x4 rows: W {4 * wl.m}x{wl.n}", "batches": {}}
+    for B in (8, 64, 256):
+        if B not in base:
+            continue
+        xg, _ = x_tensor(torch, wl, B, dev)
+        r, runner = measure_spmm(xe, torch, tall, xg, B, 4 * wl.m, wl.n, args, max(100, args.sweep_steps // 2), 20)
+        y_tall = runner.ys[0]
+        t1, t4 = base[B]["us_per_launch_events"], r["us_per_launch_events"]
+        dt = max(t4 - t1, 1e-9) * 1e-6
+        ent = {"us_m": t1, "us_4m": t4, "tflops_4m": r["tflops"], "compressed_gbs_4m": r["compressed_gbs"],
+               "marginal_tflops": 2.0 * 3 * wl.m * wl.n * B / dt / 1e12,
+               "marginal_gbs": 3.0 * base[B]["compressed_bytes"] / dt / 1e9}
+        ent["marginal_frac"] = (ent["marginal_tflops"] / MFMA_BF16_PEAK_TFLOPS if B >= 32
+                                else ent["marginal_gbs"] / HBM_PEAK_GBS)
+        ent["marginal_bound"] = "mfma" if B >= 32 else "hbm"
+        ent["rows_repeat_bit_exactly"] = bool(torch.equal(y_tall[:wl.m], y_tall[wl.m:2 * wl.m]))
+        res["batches"][f"B{B}"] = ent
+        del runner
+    del tall
+    torch.cuda.empty_cache()
     return res
 
 
@@ -259,16 +393,11 @@ def wide_extra(xe, torch, dev, args, base_cfg, n_in=24):
     res = {"workload": f"{cfg.name}: W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in={n_in} n_out=192 bf16",
            "compressed_bytes": layer.compressed_bytes(), "patches": int(layer.patch.numel())}
     for B in (8, 64):
-        stored, _ = wl.X(B)
-        xg = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev)
-        runner = SpmmRunner(xe, torch, layer, xg, B, args.replica_bytes)
-        if not args.no_graph:
-            runner.capture()
-        steps = max(200, args.sweep_steps)
-        wall, ev = runner.time(steps, 50)
-        res[f"B{B}_us_per_launch"] = ev * 1e6 / steps
-        res[f"B{B}_tflops"] = 2.0 * cfg.m * cfg.n * B * steps / wall / 1e12
-        res[f"B{B}_compressed_gbs"] = runner.comp_bytes * steps / wall / 1e9
+        xg, _ = x_tensor(torch, wl, B, dev)
+        r, runner = measure_spmm(xe, torch, layer, xg, B, cfg.m, cfg.n, args, max(200, args.sweep_steps), 50)
+        res[f"B{B}_us_per_launch"] = r["us_per_launch_events"]
+        res[f"B{B}_tflops"] = r["tflops"]
+        res[f"B{B}_compressed_gbs"] = r["compressed_gbs"]
         del runner
     return res
 
@@ -292,7 +421,7 @@ def storage_extra(xe, layer):
 def encoder_extra(xe, torch, dev, base_cfg):
     """Both GPU encoders (Algorithm 1; the 2^n_in search of Section 5.2) on the default matrix, at its own
     slice geometry and at n_out = 128 / n_in = 16.  Times are host wall-clock around the binding call
-    (buffer allocation, three kernels, one synchronisation to read the patch total), best of three."""
+    (buffer allocation, the kernels, one synchronisation to read the patch total), best of three."""
     import dataclasses
 
     from synth_inputs import make_workload
@@ -341,55 +470,26 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
-    def x_for(B):
-        stored, exact = wl.X(B)
-        if cfg.x_dtype == "bf16":
-            return torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).to(dev), exact
-        return torch.from_numpy(stored).to(dev), exact
-
-    def measure(B, steps, warmup):
-        xg, xexact = x_for(B)
-        runner = SpmmRunner(xe, torch, layer, xg, B, args.replica_bytes)
-        if not args.no_graph:
-            runner.capture()
-        wall, ev = runner.time(steps, warmup)
-        flops = 2.0 * wl.m * wl.n * B
-        res = {"B": B, "ms_per_step": wall * 1e3 / steps, "us_per_launch_events": ev * 1e6 / steps,
-               "tflops": flops * steps / wall / 1e12, "compressed_gbs": runner.comp_bytes * steps / wall / 1e9,
-               "replicas": runner.R, "step_bytes": runner.step_bytes, "compressed_bytes": runner.comp_bytes,
-               "roofline": roofline_entry(flops, runner.comp_bytes, runner.step_bytes, ev / steps, B)}
-        tr = MEASURED_TRAFFIC.get(f"{cfg.name}:B{B}")
-        if tr is not None:      # HBM bytes per launch (read + written), rocprofv3 counters scaled by a known copy
-            res["roofline"]["traffic"] = tr["read_bytes"] + tr["write_bytes"]
-            res["roofline"]["traffic_read_bytes"] = tr["read_bytes"]
-            res["roofline"]["traffic_write_bytes"] = tr["write_bytes"]
-        return res, runner, xexact
-
-    main_res, runner, xexact = measure(args.batch, args.steps, args.warmup)
+    xg, xexact = x_tensor(torch, wl, args.batch, dev)
+    main_res, runner = measure_spmm(xe, torch, layer, xg, args.batch, wl.m, wl.n, args, args.steps, args.warmup,
+                                    workload=cfg.name)
     y0 = runner.ys[0].cpu().numpy()
+    del runner
 
+    by_batch = {args.batch: main_res}
     sweep = []
     for tok in [t for t in args.sweep.split(",") if t.strip()]:
         B = int(tok)
         if B == args.batch or B not in cfg.batches:
             continue
-        r, _, _ = measure(B, args.sweep_steps, max(10, args.sweep_steps // 10))
+        xs, _ = x_tensor(torch, wl, B, dev)
+        r, rn = measure_spmm(xe, torch, layer, xs, B, wl.m, wl.n, args, args.sweep_steps,
+                             max(10, args.sweep_steps // 10), workload=cfg.name)
+        del rn
         sweep.append(r)
+        by_batch[B] = r
 
-    extra = {}
-    if args.decode_only:
-        out = xe.decode(layer, xe.OUT_PLANES)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(200):
-            xe.decode(layer, xe.OUT_PLANES, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / 200
-        extra["decode_planes_us"] = us
-        extra["decode_planes_gbs"] = (layer.compressed_bytes() + out.numel() * 8) / (us * 1e-6) / 1e9
-
+    weights = float(cfg.m) * cfg.n
     out = {
         "metric": "fused decode+SpMM TFLOP/s & compressed-HBM GB/s (% roofline) at 1 MI355X",
         "value": main_res["tflops"], "unit": "TFLOP/s (dense-equivalent 2*m*n*B per step)",
@@ -397,22 +497,39 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.x_dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in={cfg.n_in} n_out=64, "
                                f"X {cfg.n}x{args.batch} {cfg.x_dtype}",
-                   "B": args.batch, "replicas": main_res["replicas"], "graph": not args.no_graph,
+                   "B": args.batch, "replicas": main_res["replicas"],
+                   "graph": bool(main_res["graph_replays"] > 0), "graph_replays": main_res["graph_replays"],
                    "patches": int(layer.patch.numel()), "compressed_bytes": main_res["compressed_bytes"],
-                   "setup_seconds": t_gen},
+                   "setup_seconds": t_gen, "kernel_sources_digest": kernel_source_digest()},
         "compressed_hbm_gbs": main_res["compressed_gbs"],
         "us_per_launch": main_res["us_per_launch_events"],
         "roofline": main_res["roofline"],
         "sweep": sweep,
     }
-    if not args.no_fig1 and cfg.name != "fig1":
-        extra["fig1"] = fig1_extra(xe, torch, dev, args)
+    extra = {}
+    if not args.no_configs:
+        mine = {"workload": f"W {cfg.m}x{cfg.n} S={cfg.S} q={cfg.q} n_in={cfg.n_in} n_out={cfg.n_out}, X {cfg.x_dtype}",
+                "compressed_bytes": layer.compressed_bytes(), "patches": int(layer.patch.numel()),
+                "patches_per_slice": float(layer.patch.numel()) / (cfg.q * cfg.m * -(-cfg.n // cfg.n_out)),
+                "stored_bits_per_weight": 8.0 * layer.compressed_bytes() / weights,
+                "encrypted_bits_per_weight": 8.0 * layer.enc.numel() / weights,
+                "batches": {f"B{B}": {k: r[k] for k in ("us_per_launch_events", "tflops", "compressed_gbs", "replicas",
+                                                        "graph_replays", "roofline")}
+                            for B, r in sorted(by_batch.items())}}
+        extra["configs"] = config_table(xe, torch, dev, args, {cfg.name: mine})
+    if not args.no_marginal and cfg.m % 32 == 0 and cfg.m * 4 * cfg.n <= (1 << 29):
+        extra["marginal"] = marginal_rates(xe, torch, dev, args, wl, layer, by_batch)
+    if not args.no_fig1 and cfg.name != "fig1" and args.no_configs:
+        from synth_inputs import make_workload as mk
+        f1 = mk(CONFIGS["fig1"])
+        l1 = build_layer(f1, xe, torch, dev)
+        extra["fig1"] = {"decode": decode_times(xe, torch, l1, args, ((xe.OUT_PLANES, "planes"), (xe.OUT_BF16, "bf16")))}
     if not args.no_wide and cfg.n_out == 64:
         extra["n_out_192"] = wide_extra(xe, torch, dev, args, cfg)
         extra["n_out_192_n_in_20"] = wide_extra(xe, torch, dev, args, cfg, n_in=20)
     extra["storage"] = storage_extra(xe, layer)
     if not args.no_decode:
-        extra["decode"] = decode_extra(xe, torch, layer)
+        extra["decode"] = decode_times(xe, torch, layer, args)
     if not args.no_encoder:
         extra["encoder"] = encoder_extra(xe, torch, dev, cfg)
     if args.copy_calibration:
