@@ -49,6 +49,8 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n),
                "s"(l_spr), "s"(l_nrb), "s"(l_n_units), "s"(l_q), "s"(n_in), "s"(l_n_slots), "s"(X), "s"(ldx), "s"(B), "s"(Y),
                "s"(ldy), "s"(slices_per_split), "s"(n_splits));
+  // a wave that is still setting up goes before the waves that are already in their loops
+  __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -123,26 +125,51 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
     }
   }
 
-  // ---- X^T of the workgroup's reduction range into LDS, in operand-slot order.  Element (k, b):
-  // k = s_begin*64 + kl, position of kl inside its slice: half g' = bit 5, dword d = bits 3..4,
-  // high code = bit 2, e = bit 1, par = bit 0  ->  g'*32 + (2 par + e)*8 + 2 d + high.
+  // ---- X^T into LDS, in operand-slot order.  Element (k, b): k = s_begin*64 + kl, position of kl inside its
+  // slice: half g' = bit 5, dword d = bits 3..4, high code = bit 2, e = bit 1, par = bit 0
+  //   ->  g'*32 + (2 par + e)*8 + 2 d + high.
+  // Every wave stages the part that its own slices need (nobody else reads it, so no barrier follows):
+  // lane = position inside the slice, four slices per round with their loads issued together.
   const bool row16 = B == 8 && (ldx & 7) == 0 && (reinterpret_cast<uintptr_t>(X) & 15) == 0;  // uniform
-  for (int kl = tid; kl < range_k; kl += NW * 64) {
-    const int kk = kl & 63;
-    const int pos = (kl & ~63) + (kk & 32) + (((kk & 1) * 2 + ((kk >> 1) & 1)) * 8) + ((kk >> 3) & 3) * 2 + ((kk >> 2) & 1);
-    const int64_t k = (int64_t)s_begin * 64 + kl;
-    uint8_t *dst = xt_all + pos * 2;
-    if (row16) {  // one 16-byte load per X row
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (k < l_n) v = *reinterpret_cast<const uint4 *>(X + k * ldx);
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  {
+    const int kk = lane;
+    const int pos_in_slice = (kk & 32) + (((kk & 1) * 2 + ((kk >> 1) & 1)) * 8) + ((kk >> 3) & 3) * 2 + ((kk >> 2) & 1);
+    // buffer loads: rows beyond the end of X (and the slots of a last, short round) read as zero through the
+    // range check, so the loads of a round carry no branches and go out together
+    const uint32_t x_extent = (uint32_t)(((int64_t)(l_n - 1) * ldx + B) * 2);
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(X), 0, x_extent, kRsrcFlags);
+    const uint32_t row_bytes = (uint32_t)(ldx * 2);
+    for (int i0 = 0; i0 < cnt; i0 += 4) {  // uniform
+      const int nj = min(4, cnt - i0);
+      uint32_t off[4];
 #pragma unroll
-      for (int b = 0; b < 8; ++b)
-        *reinterpret_cast<uint16_t *>(dst + b * xstride) = (uint16_t)(w[b >> 1] >> (16 * (b & 1)));
-    } else {
-      for (int b = 0; b < B; ++b) {  // uniform
-        const uint16_t v = (k < l_n) ? X[k * ldx + b] : (uint16_t)0;
-        *reinterpret_cast<uint16_t *>(dst + b * xstride) = v;
+      for (int j = 0; j < 4; ++j) {
+        const int64_t k = (int64_t)(w0 + i0 + j) * 64 + kk;
+        off[j] = (j < nj && k < l_n) ? (uint32_t)k * row_bytes : 0xFFFFFFF0u;  // beyond the extent: reads zero
+      }
+      if (row16) {  // one 16-byte load per X row
+        u32x4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off[j], 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (j >= nj) break;  // uniform
+          uint8_t *dst = xt_all + ((w0 - s_begin + i0 + j) * 64 + pos_in_slice) * 2;
+#pragma unroll
+          for (int b = 0; b < 8; ++b)
+            *reinterpret_cast<uint16_t *>(dst + b * xstride) = (uint16_t)(v[j][b >> 1] >> (16 * (b & 1)));
+        }
+      } else {
+        for (int b = 0; b < B; ++b) {  // uniform
+          uint16_t v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, off[j], (uint32_t)(2 * b), 0);
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (j < nj)
+              *reinterpret_cast<uint16_t *>(xt_all + ((w0 - s_begin + i0 + j) * 64 + pos_in_slice) * 2 + b * xstride) = v[j];
+        }
       }
     }
   }
@@ -182,7 +209,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
     const int p = i / ROWS, r = row0 + i % ROWS;
     alpha_s[i] = (r < l_m) ? -0.5f * l_alpha[(int64_t)p * l_m + r] : 0.f;
   }
-  __syncthreads();  // X^T, the tables and alpha are in place
+  if constexpr (!PRIV_LUT) __syncthreads();  // shared tables; X^T is private to the wave, alpha is read after the loop
 
   // ---- patch entries of the range: lane j holds the j-th entry
   uint32_t offrel[RB][Q], entv[RB][Q];
@@ -246,6 +273,7 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
     bf16x8 xa[2][4];
     read_xa(w0, xa[0]);
     lookup(ring[0], Snext);
+    __builtin_amdgcn_s_setprio(0);
     for (int sb = w0; sb < w1; sb += 2) {
 #pragma unroll
       for (int d = 0; d < 2; ++d) {
