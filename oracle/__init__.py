@@ -10,7 +10,7 @@ Everything here follows "Structured Compression by Weight Encryption for
 Unstructured Pruning and Quantization" (arXiv 1905.10138):
 
   gf2.py           XOR-gate network y = M x over GF(2) (Section 3.1)
-  patch_search.py  Algorithm 1 written out step by step, make_rref, and the
+  patch_search.py  Algorithm 1 one slice at a time (row_reduce per request), and the
                    exhaustive 2^n_in search of Section 5.2 (small inputs only)
   encoder.py       slicing (Section 3.1), Algorithm 1 in incremental-elimination
                    form vectorised over slices, the compressed format of Section 3.2

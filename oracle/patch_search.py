@@ -1,4 +1,4 @@
-"""Algorithm 1 (Patch-Searching) step by step, and the exhaustive search of Section 5.2.
+"""Algorithm 1 of Section 3.3 (patch searching) one slice at a time, and the exhaustive search of Section 5.2.
 
 Test infrastructure; small inputs only (pure Python loops).  One slice at a time, in
 the paper's notation: w^q in {0, x, 1}^n_out given as (care, bits), M in {0,1}^(n_out x n_in).
@@ -8,73 +8,71 @@ import numpy as np
 from .gf2 import xor_network
 
 
-def make_rref(mat: np.ndarray) -> np.ndarray:
-    """Reduced row-echelon form over GF(2) of an augmented matrix (k, n_in + 1).
+def row_reduce(system: np.ndarray) -> np.ndarray:
+    """Reduced row-echelon form over GF(2) of a system [coefficients | right-hand side], shape (k, n_in + 1).
 
-    Pivots are searched in the first n_in columns only (the last column is the
-    right-hand side), from the lowest column index up.  Zero rows sink to the bottom.
+    Only the n_in coefficient columns can hold a pivot; they are scanned from the lowest index up.
+    Rows without a pivot end up below the others.
     """
-    a = np.array(mat, dtype=np.uint8) & 1
-    k, ncol = a.shape
-    r = 0
-    for c in range(ncol - 1):
-        piv = None
-        for i in range(r, k):
-            if a[i, c]:
-                piv = i
-                break
-        if piv is None:
+    a = np.array(system, dtype=np.uint8) & 1
+    n_rows, n_cols = a.shape
+    top = 0                                           # rows above `top` already own a pivot
+    for col in range(n_cols - 1):
+        below = np.flatnonzero(a[top:, col])
+        if below.size == 0:
             continue
-        if piv != r:
-            a[[r, piv]] = a[[piv, r]]
-        for i in range(k):
-            if i != r and a[i, c]:
-                a[i] ^= a[r]
-        r += 1
-        if r == k:
+        src = top + int(below[0])
+        if src != top:
+            a[[top, src]] = a[[src, top]]
+        others = np.flatnonzero(a[:, col])
+        others = others[others != top]
+        a[others] ^= a[top]                           # clear the column everywhere else
+        top += 1
+        if top == n_rows:
             break
     return a
 
 
-def is_solved(rref: np.ndarray) -> bool:
-    """The system is solvable iff no row reads 0 ... 0 | 1 (Section 3.3)."""
-    coef = rref[:, :-1]
-    rhs = rref[:, -1]
-    return not bool(np.any((coef.sum(axis=1) == 0) & (rhs == 1)))
+def has_solution(reduced: np.ndarray) -> bool:
+    """A reduced system is solvable unless one of its rows says 0 = 1 (Section 3.3)."""
+    empty_left = ~reduced[:, :-1].any(axis=1)
+    return not bool((empty_left & (reduced[:, -1] == 1)).any())
 
 
-def solve_free_zero(rref: np.ndarray, n_in: int) -> np.ndarray:
-    """A solution of a consistent RREF system with every free variable set to 0."""
+def solution_with_free_zero(reduced: np.ndarray, n_in: int) -> np.ndarray:
+    """The solution of a solvable reduced system in which every variable without a pivot is 0."""
     x = np.zeros(n_in, dtype=np.uint8)
-    for row in rref:
-        nz = np.flatnonzero(row[:-1])
-        if nz.size:
-            x[nz[0]] = row[-1]
+    for row in reduced:
+        cols = np.flatnonzero(row[:-1])
+        if cols.size:
+            x[cols[0]] = row[-1]
     return x
 
 
 def patch_search(care: np.ndarray, bits: np.ndarray, M: np.ndarray):
-    """Algorithm 1.  Returns (n_patch, d_patch, w_c, dropped).
+    """Algorithm 1, Section 3.3.  Returns (n_patch, d_patch, w_c, dropped).
 
-    care, bits: length-n_out arrays; bits is only read where care is set.
+    care, bits: length-n_out arrays; bits is only read where care is set.  Every kept weight i asks for
+    (row i of M) . w^c = bits[i]; the requests are taken in ascending position and one is accepted only if
+    the accepted ones together with it can still be met.  w^c then solves the accepted requests, and the
+    patches are the kept positions that M w^c gets wrong.
     d_patch: ascending 0-based positions to flip after decryption.
-    dropped: the care positions whose equation was removed inside the loop.
+    dropped: the kept positions whose request was refused.
     """
     M = np.asarray(M, dtype=np.uint8)
     n_out, n_in = M.shape
-    mat = np.zeros((0, n_in + 1), dtype=np.uint8)
+    wanted = [1 if bits[i] else 0 for i in range(n_out)]
+    accepted = np.zeros((0, n_in + 1), dtype=np.uint8)      # one row [M_i | wanted bit] per accepted request
     dropped = []
-    for i in np.flatnonzero(care):                       # only not-pruned bits, ascending
-        row = np.concatenate([M[i], [1 if bits[i] else 0]]).astype(np.uint8)
-        mat = np.vstack([mat, row[None, :]])             # append (M_i1 .. M_i,n_in, w_i)
-        rref = make_rref(mat)
-        if not is_solved(rref):
-            mat = mat[:-1]                               # remove the last row again
+    for i in np.flatnonzero(care):
+        trial = np.vstack([accepted, np.append(M[i], wanted[i]).astype(np.uint8)[None, :]])
+        if has_solution(row_reduce(trial)):
+            accepted = trial
+        else:
             dropped.append(int(i))
-    rref = make_rref(mat) if mat.shape[0] else mat
-    w_c = solve_free_zero(rref, n_in)
-    w_dd = xor_network(M, w_c)                           # decrypted slice
-    d_patch = [int(i) for i in np.flatnonzero(care) if w_dd[i] != (1 if bits[i] else 0)]
+    w_c = solution_with_free_zero(row_reduce(accepted), n_in) if accepted.shape[0] else np.zeros(n_in, np.uint8)
+    decrypted = xor_network(M, w_c)
+    d_patch = [int(i) for i in np.flatnonzero(care) if decrypted[i] != wanted[i]]
     return len(d_patch), d_patch, w_c, dropped
 
 

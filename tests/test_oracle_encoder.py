@@ -15,15 +15,15 @@ def _random_slice(rng, n_out, p_care):
     return care, bits
 
 
-def test_make_rref_textbook_case():
+def test_row_reduce_textbook_case():
     # x0 ^ x1 = 1, x1 ^ x2 = 0, x0 ^ x2 = 1 (dependent, consistent)
     mat = np.array([[1, 1, 0, 1], [0, 1, 1, 0], [1, 0, 1, 1]], dtype=np.uint8)
-    r = patch_search.make_rref(mat)
+    r = patch_search.row_reduce(mat)
     assert r.tolist() == [[1, 0, 1, 1], [0, 1, 1, 0], [0, 0, 0, 0]]
-    assert patch_search.is_solved(r)
+    assert patch_search.has_solution(r)
     mat[2, 3] = 0                                   # now x0 ^ x2 = 0: contradiction
-    assert not patch_search.is_solved(patch_search.make_rref(mat))
-    assert patch_search.solve_free_zero(r, 3).tolist() == [1, 0, 0]
+    assert not patch_search.has_solution(patch_search.row_reduce(mat))
+    assert patch_search.solution_with_free_zero(r, 3).tolist() == [1, 0, 0]
 
 
 def test_fig4_structure(golden):
