@@ -130,7 +130,6 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
   //   ->  g'*32 + (2 par + e)*8 + 2 d + high.
   // Every wave stages the part that its own slices need (nobody else reads it, so no barrier follows):
   // lane = position inside the slice, four slices per round with their loads issued together.
-  const bool row16 = B == 8 && (ldx & 7) == 0 && (reinterpret_cast<uintptr_t>(X) & 15) == 0;  // uniform
   {
     const int kk = lane;
     const int pos_in_slice = (kk & 32) + (((kk & 1) * 2 + ((kk >> 1) & 1)) * 8) + ((kk >> 3) & 3) * 2 + ((kk >> 2) & 1);
@@ -148,28 +147,14 @@ __global__ __launch_bounds__(NW * 64) void spmm_small_kernel(DevLayer L, const u
         const int64_t k = (int64_t)(w0 + i0 + j) * 64 + kk;
         off[j] = (j < nj && k < l_n) ? (uint32_t)k * row_bytes : 0xFFFFFFF0u;  // beyond the extent: reads zero
       }
-      if (row16) {  // one 16-byte load per X row
-        u32x4 v[4];
+      for (int b = 0; b < B; ++b) {  // uniform
+        uint16_t v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off[j], 0, 0);
+        for (int j = 0; j < 4; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, off[j], (uint32_t)(2 * b), 0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (j >= nj) break;  // uniform
-          uint8_t *dst = xt_all + ((w0 - s_begin + i0 + j) * 64 + pos_in_slice) * 2;
-#pragma unroll
-          for (int b = 0; b < 8; ++b)
-            *reinterpret_cast<uint16_t *>(dst + b * xstride) = (uint16_t)(v[j][b >> 1] >> (16 * (b & 1)));
-        }
-      } else {
-        for (int b = 0; b < B; ++b) {  // uniform
-          uint16_t v[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, off[j], (uint32_t)(2 * b), 0);
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (j < nj)
-              *reinterpret_cast<uint16_t *>(xt_all + ((w0 - s_begin + i0 + j) * 64 + pos_in_slice) * 2 + b * xstride) = v[j];
-        }
+        for (int j = 0; j < 4; ++j)
+          if (j < nj)
+            *reinterpret_cast<uint16_t *>(xt_all + ((w0 - s_begin + i0 + j) * 64 + pos_in_slice) * 2 + b * xstride) = v[j];
       }
     }
   }
