@@ -99,7 +99,9 @@ struct BoolC {
 // JT = most 64-bit words per slice the variant has table space for: 1 (n_out = 64) or 4 (n_out up to 256).
 // PD = slice buffers per wave on the direct path: 2 (loads a slice and a half ahead, two waves per
 // SIMD hide each other's waits) or 1 (loads one slice ahead, more waves per SIMD do the hiding).
-template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
+// NARROW: at most eight columns of X (one 16-byte chunk per row): a slice of X is 1 KB and arrives with a
+// single direct load; the operand lanes of the 24 padding columns read the same chunk again.
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT, bool NARROW = false>
 __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void spmm_kernel(DevLayer L, const void *__restrict__ Xv, int64_t ldx, int B,
                                                       float *__restrict__ Y, int64_t ldy, int slices_per_split,
                                                       int n_splits) {
@@ -108,7 +110,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
   // staging); the wave then owns two unpadded, swizzled slice buffers.  Otherwise X passes through
   // registers into one padded buffer.
   constexpr bool XDIR = XFAST && !XF32;
-  constexpr int RSB = XDIR ? CW * 2 : CW * 2 + 16;  // LDS row stride in bytes
+  static_assert(!NARROW || (XDIR && NCB == 1), "narrow rows of X exist on the direct path with one column block");
+  constexpr int RSB = NARROW ? 16 : XDIR ? CW * 2 : CW * 2 + 16;  // LDS row stride in bytes
   constexpr int XSL = 64 * RSB;                     // the 64 X rows of one slice
   constexpr int KC = RB * (1 + Q * (NIBT == 3 ? 2 : 1));  // compressed dwords per lane and slice (XDIR)
   // With one slice buffer the staging area also takes the patch offsets of the wave's range (one dword
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
   constexpr int XBUF = XDIR ? PD * (XSL + CSL) : XSL;     // one wave's LDS share (PD slice buffers)
   constexpr int ROWS = 32 * RB;
   constexpr int NR = XF32 ? CW / 3 : CW;       // real X columns per workgroup
-  constexpr int NCH = XF32 ? NR / 4 : CW / 8;  // 16-byte chunks per X row in global memory
+  constexpr int NCH = NARROW ? 1 : XF32 ? NR / 4 : CW / 8;  // 16-byte chunks per X row in global memory
   constexpr int RPI = 64 / NCH;                // rows covered by one load instruction of the wave (XFAST)
   constexpr int EPC = XF32 ? 4 : 8;            // X elements per chunk
   constexpr int ESZ = XF32 ? 4 : 2;            // bytes per X element
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
     return ((pos & 1) << 2) | (((pos >> 1) & 1) << 3) | ((pos >> 2) & 1) | (((pos >> 3) & 1) << 1) |
            (((pos >> 4) & 1) << 4) | (((pos >> 5) & 1) << 5);
   };
-  auto swz_of_pos = [](int pos) { return (NCH == 8) ? ((pos & 3) << 1) : (((pos >> 1) & 1) << 1); };
+  auto swz_of_pos = [](int pos) { return NARROW ? 0 : (NCH == 8) ? ((pos & 3) << 1) : (((pos >> 1) & 1) << 1); };
   const int xrow = XDIR ? row_of_pos(lane / NCH) : (XFAST ? lane / NCH : lane);
   const int xch = XDIR ? ((lane % NCH) ^ swz_of_pos(lane / NCH)) : (XFAST ? lane % NCH : 0);
   const uint32_t x_lane_off = (uint32_t)(xrow * row_bytes) + ((col0 + xch * EPC < B) ? xch * 16 : 0);
@@ -548,7 +551,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
     const int pos_lane = jj | (g << 5);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
-      const int c = 4 * cb + 2 * ((lane >> 4) & 1) + (c4 >> 1);
+      const int c = NARROW ? 0 : 4 * cb + 2 * ((lane >> 4) & 1) + (c4 >> 1);
       tr_off[cb] = (uint32_t)(pos_lane * RSB + ((c ^ swz_of_pos(pos_lane)) * 16) + 8 * (c4 & 1));
     }
   }
@@ -909,16 +912,16 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
   }
 }
 
-template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT>
+template <int NCB, int Q, int RB, bool XF32, int NW, bool XFAST, int PD, int NIBT, int JT, bool NARROW = false>
 inline void launch_variant(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, dim3 grid,
                            int sps, int n_splits, hipStream_t st) {
-  hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, XFAST, PD, NIBT, JT>), grid, dim3(NW * 64), 0, st, D, X, ldx, B,
-                     Y, ldy, sps, n_splits);
+  hipLaunchKernelGGL((spmm_kernel<NCB, Q, RB, XF32, NW, XFAST, PD, NIBT, JT, NARROW>), grid, dim3(NW * 64), 0, st, D, X,
+                     ldx, B, Y, ldy, sps, n_splits);
 }
 
 // XMODE: 0 = the call site may see either layout, 1 = aligned X only, 2 = generic X only (keeps
 // variants that are never launched from being compiled)
-template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2, int XMODE = 0, int JMODE = 0>
+template <int NCB, int Q, int RB, bool XF32, int NW = 8, int PD = 2, int XMODE = 0, int JMODE = 0, bool NARROW = false>
 int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, int x_fast,
                     hipStream_t st) {
   constexpr int NR = XF32 ? (32 * NCB) / 3 : 32 * NCB;
@@ -961,16 +964,16 @@ int32_t launch_spmm(const DevLayer &D, const void *X, int64_t ldx, int B, float 
         }
     if constexpr (JMODE != 4)
       if (!wide) switch (D.nib) {
-          case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
-          case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 1: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 1, 1, NARROW>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
+          case 2: launch_variant<NCB, Q, RB, XF32, NW, true, PD, 2, 1, NARROW>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st); break;
           case 3:
             // (the four-wave workgroups that share a CU have LDS for one or two tables per wave only)
             if constexpr (NW == 4 && !XF32) return XORENC_EUNSUPPORTED;
-            else launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+            else launch_variant<NCB, Q, RB, XF32, NW, true, PD, 3, 1, NARROW>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
             break;
           default:
             if constexpr (NW == 4 && !XF32) return XORENC_EUNSUPPORTED;
-            else launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4, 1>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
+            else launch_variant<NCB, Q, RB, XF32, NW, true, PD, 4, 1, NARROW>(D, X, ldx, B, Y, ldy, grid, sps, atomic, st);
             break;
         }
   }
@@ -994,6 +997,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
       if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
       return launch_spmm<2, Q, 2, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     }
+    if (B <= 8 && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill most of the chip.
     // Up to 256 of them run as eight-wave workgroups, one per CU, in a single round; more run as
@@ -1005,6 +1009,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     if (D.J == 1 && tiles128 >= 200) return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
+    if (B <= 8 && x_fast && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1 && x_fast) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (!x_fast) return launch_spmm<2, Q, 1, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
@@ -1018,6 +1023,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 3) {
     // (12 waves with one slice buffer: measured 13.2 against 18.9 us with 8 waves and two buffers, 6000 x 3000, B = 32)
+    if (B <= 8 && x_fast && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (x_fast) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else {
