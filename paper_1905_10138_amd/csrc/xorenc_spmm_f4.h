@@ -560,6 +560,9 @@ bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ld
   if (P.rounds == 1) {
     *rc = launch_f4<Q, PMAX, false>(D, X, ldx, B, Y, ldy, P, st);
   } else {
+    // several planes and only twice the pieces one round takes: the halved range per wave would double the rounds
+    // again, and the other kernels are as fast there
+    if (Q >= 2 && P.rounds == 2) return false;
     if (!f4_plan(D, B, PMAX2, &P)) return false;
     *rc = launch_f4<Q, PMAX2, true>(D, X, ldx, B, Y, ldy, P, st);
   }
