@@ -313,6 +313,130 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Bit-plane output, slices of one 64-bit word: a leaner kernel of its own.  A wave takes one run of eight
+// consecutive word positions of one row block and never meets another wave after the tables are built: lane
+// (row rr = lane%32, h = lane/32) decodes words 4h .. 4h+3 of the run for its row, so its four results are 32
+// consecutive bytes of the row-major output and the two lanes of a row cover 64.  Everything the run needs is
+// requested before the tables are built; the patch entries of the whole run (one contiguous list) are fetched
+// with one load, lane j = entry j, and scattered into a per-wave area of flip words that each lane then reads.
+template <int Q>
+__global__ __launch_bounds__(256) void decode_planes_kernel(DevLayer L, uint64_t *__restrict__ out, int runs_per_rb) {
+  __shared__ uint2 lut[4 * 256];             // T_b[v], b < nib
+  __shared__ uint64_t flips[4][Q][4][64];    // per wave: plane, word of the lane, lane
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rr = lane & 31, h = lane >> 5;
+  const int run = blockIdx.x * 4 + wave;
+  const int rb = run / runs_per_rb, s_base = (run - rb * runs_per_rb) * 8;
+  const bool live = rb < L.nrb;  // uniform per wave
+  const int n_in = L.n_in, spr = L.spr;
+  // ---- requests.  The nine patch offsets of the run (per plane) go first: loads return in order, and their
+  // answer starts the only dependent request (the patch entries), which then travels with the bulk of the run.
+  uint64_t keep[4];
+  uint32_t x[Q][4], offv[Q];
+#pragma unroll
+  for (int p = 0; p < Q; ++p) {
+    offv[p] = 0u;
+    // lane j: offset of the list of word s_base + j (clamped to the row block's end: later words have no entries)
+    if (live && lane <= 8) offv[p] = L.patch_off[(int64_t)p * L.n_units + (int64_t)rb * spr + min(s_base + lane, spr)];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int s = s_base + 4 * h + i;
+    keep[i] = 0ull;
+#pragma unroll
+    for (int p = 0; p < Q; ++p) x[p][i] = 0u;
+    if (live && s < spr) {
+      const int64_t slot = ((int64_t)rb * spr + s) * 32 + rr;
+      keep[i] = *reinterpret_cast<const uint64_t *>(L.mask32 + 2 * slot);
+#pragma unroll
+      for (int p = 0; p < Q; ++p) x[p][i] = load_enc(L.enc, (int64_t)p * L.n_eslots + slot, n_in);
+    }
+  }
+  // entries of the run's lists, lane j = entry j (the first 64; longer lists are read in further trips below)
+  uint32_t ent[Q], ebase[Q], etotal[Q];
+#pragma unroll
+  for (int p = 0; p < Q; ++p) {
+    ebase[p] = __builtin_amdgcn_readlane(offv[p], 0);
+    etotal[p] = __builtin_amdgcn_readlane(offv[p], 8) - ebase[p];
+    ent[p] = 0u;
+    if ((uint32_t)lane < etotal[p]) ent[p] = L.patch[ebase[p] + lane];
+  }
+  // ---- tables (shared by the four waves) and this wave's flip words
+  for (int b = 0; b < L.nib; ++b) {  // uniform
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const uint32_t on = 0u - ((threadIdx.x >> t) & 1u);
+      lo ^= L.Mcol_lo[8 * b + t] & on;
+      hi ^= L.Mcol_hi[8 * b + t] & on;
+    }
+    lut[b * 256 + threadIdx.x] = make_uint2(lo, hi);
+  }
+#pragma unroll
+  for (int p = 0; p < Q; ++p)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) flips[wave][p][i][lane] = 0ull;
+  __syncthreads();
+  if (!live) return;
+  // ---- patch entries -> flip words.  Entry j of the run's list belongs to word t = number of list ends <= j.
+#pragma unroll
+  for (int p = 0; p < Q; ++p) {
+    const uint32_t base = ebase[p], total = etotal[p];
+    uint32_t ends[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) ends[t] = __builtin_amdgcn_readlane(offv[p], t + 1) - base;
+    for (uint32_t j0 = 0; j0 < total; j0 += 64u) {  // uniform; one trip unless the lists are very long
+      const uint32_t j = j0 + (uint32_t)lane;
+      if (j < total) {
+        const uint32_t v = j0 ? (uint32_t)L.patch[base + j] : ent[p];  // (row%32) << 6 | bit
+        uint32_t t = 0;
+#pragma unroll
+        for (int k = 0; k < 7; ++k) t += j >= ends[k] ? 1u : 0u;
+        // word t of the run is word t%4 of the lane (row, t/4)
+        atomicXor(reinterpret_cast<unsigned long long *>(&flips[wave][p][t & 3][(v >> 6) + 32u * (t >> 2)]),
+                  1ull << (v & 63u));
+      }
+    }
+  }
+  // ---- decode, patch, mask; the lane's four words of a plane leave as 32 consecutive bytes
+  const int r = rb * 32 + rr;
+  const int s0 = s_base + 4 * h;
+#pragma unroll
+  for (int p = 0; p < Q; ++p) {
+    uint64_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint2 acc = lut[x[p][i] & 255u];
+      for (int b = 1; b < L.nib; ++b) {  // uniform
+        const uint2 e = lut[b * 256 + ((x[p][i] >> (8 * b)) & 255u)];
+        acc.x ^= e.x;
+        acc.y ^= e.y;
+      }
+      w[i] = (((uint64_t)acc.y << 32 | acc.x) ^ flips[wave][p][i][lane]) & keep[i];
+    }
+    if (r < L.m && s0 < spr) {
+      uint64_t *dst = out + ((int64_t)p * L.m + r) * spr + s0;
+      if (s0 + 3 < spr && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+        *reinterpret_cast<ulonglong2 *>(dst) = make_ulonglong2(w[0], w[1]);
+        *reinterpret_cast<ulonglong2 *>(dst + 2) = make_ulonglong2(w[2], w[3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (s0 + i < spr) dst[i] = w[i];
+      }
+    }
+  }
+}
+
+template <int Q>
+void launch_decode_planes(const DevLayer &D, void *out, hipStream_t st) {
+  const int runs_per_rb = (D.spr + 7) / 8;
+  const int64_t runs = (int64_t)runs_per_rb * D.nrb;
+  hipLaunchKernelGGL(decode_planes_kernel<Q>, dim3((unsigned)((runs + 3) / 4)), dim3(256), 0, st, D,
+                     static_cast<uint64_t *>(out), runs_per_rb);
+}
+
 }  // namespace
 
 extern "C" {
@@ -330,6 +454,16 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   const uintptr_t al = out_kind == XORENC_OUT_PLANES ? 7 : (out_kind == XORENC_OUT_F32 ? 3 : 1);
   if ((uintptr_t)out & al) return XORENC_EALIGN;
   xorenc_internal_begin_call();
+  if (out_kind == XORENC_OUT_PLANES && D.J == 1 && (int64_t)((D.spr + 7) / 8) * D.nrb < ((int64_t)1 << 32)) {
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (D.q) {
+      case 1: launch_decode_planes<1>(D, out, st); break;
+      case 2: launch_decode_planes<2>(D, out, st); break;
+      case 3: launch_decode_planes<3>(D, out, st); break;
+      default: launch_decode_planes<4>(D, out, st); break;
+    }
+    return xorenc_internal_check_launch();
+  }
   // A workgroup takes `chunks` runs of eight word positions of one row block: a couple of thousand workgroups
   // in all, so that all of them are resident at once and the tables are not built once per run.
   const int64_t rpb = (D.spr + 7) / 8;  // runs per row block
