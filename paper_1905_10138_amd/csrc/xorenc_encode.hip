@@ -177,7 +177,7 @@ __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParam
   };
   // Gray code walk: step k flips bit ctz(k); inside a group of 8 steps the flipped bits are
   // 0 1 0 2 0 1 0, and only the step into the next group needs a column chosen at run time.
-  const uint32_t groups = (1u << P.n_in) >> 3;  // n_in >= 8
+  const uint32_t groups = (1u << P.n_in) >> 3;  // n_in >= 4 (checked by the entry point): at least two groups
   for (uint32_t g = 0; g < groups; ++g) {
     if (g) {
       const int j = __builtin_ctz(g) + 3;
