@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   const uint32_t o_voff = (lane <= 2 * PMAX) ? (uint32_t)min(w_lo + lane, l_spr) * 4u : 0u;
   // pairs of this wave's K range that exist in the row (none for a wave without work)
   const int npw = active ? min(PW, max(0, (l_spr - w_lo + 1) >> 1)) : 0;
-  auto load_ring = [&](int gi, Ring &R, uint32_t(&offv)[Q]) {
+  auto load_ring = [&](int gi, Ring &R, uint32_t(&offv)[Q]) __attribute__((always_inline)) {
     const int rb = gi >> 1, h = gi & 1;
     const uint32_t u0 = (uint32_t)(rb * l_spr + w_lo);
     const uint32_t ev = h ? e_voff1 : e_voff0;
@@ -144,15 +144,16 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     uint32_t e_base[Q];
 #pragma unroll
     for (int p = 0; p < Q; ++p) e_base[p] = ((uint32_t)p * e_plane_units + u0) * e_unit_bytes;
-#pragma unroll
+#pragma clang loop unroll(full)
     for (int pp = 0; pp < PMAX; ++pp) {
-      if (pp >= npw) break;  // uniform
+      if (pp < npw) {  // uniform (no break: the trip count stays a constant and the loop unrolls)
       R.mw[pp] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_voff + (uint32_t)(pp * 512), m_base, 0);
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
         R.e0[pp][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, ev, e_base[p], 0);
         if (two_dw) R.e1[pp][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, ev + 4u, e_base[p], 0);
         e_base[p] += 2u * e_unit_bytes;
+      }
       }
     }
   };
@@ -176,8 +177,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
 
   // ---- XOR tables in operand arrangement: T_b[v] = XOR of the columns 8b..8b+7 of M selected by the bits of v;
   // entry (b, v, half g), dword d: bit 4j+3 = bit 4j+d of half g of T_b[v]
-  if (tid < NIBT * 256) {
-    const int b = __builtin_amdgcn_readfirstlane(tid >> 8), v = tid & 255;
+  for (int e0 = 0; e0 < NIBT * 256; e0 += NT) {  // uniform
+    if (e0 + tid >= NIBT * 256) break;           // whole waves: a wave lies inside one table
+    const int b = __builtin_amdgcn_readfirstlane((e0 + tid) >> 8), v = tid & 255;
     uint32_t cl[8], ch[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
 
   // ---- patch entries of a granule's range: lane j holds the j-th entry (lists of more than 64 entries are
   // read from memory pair by pair instead); their offsets have arrived long ago
-  auto load_entries = [&](const uint32_t(&offv)[Q], uint32_t(&entv)[Q], bool &fast) {
+  auto load_entries = [&](const uint32_t(&offv)[Q], uint32_t(&entv)[Q], bool &fast) __attribute__((always_inline)) {
     fast = true;
 #pragma unroll
     for (int p = 0; p < Q; ++p) {
@@ -331,9 +333,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     // the scale of slots 32 kg .. 32 kg + 31 (word kg/2 of the pair, half kg%2) comes from lane (row, kg)
     const uint8_t *ssrc = scl + (w_lo * 2 + kg) * MB + n16;
     const int wstep = 64 * MB;
-#pragma unroll
+#pragma clang loop unroll(full)
     for (int pp = 0; pp < PMAX; ++pp) {
-      if (pp >= npw) break;  // uniform
+      if (pp < npw) {  // uniform (no break: the trip count stays a constant and the loop unrolls)
       const u32x4 c0 = *reinterpret_cast<const u32x4 *>(xsrc + (2 * pp) * wstep);
       const u32x4 c1 = *reinterpret_cast<const u32x4 *>(xsrc + (2 * pp + 1) * wstep);
 #pragma unroll
@@ -342,6 +344,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
         xop[pp][4 + i] = (int)c1[i];
       }
       xsc[pp >> 2] |= (uint32_t)ssrc[pp * 4 * MB] << (8 * (pp & 3));
+      }
     }
   }
   __syncthreads();  // the operand area is free: it now takes the partial sums
@@ -355,7 +358,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   // One granule: `cur` holds its words; in double-buffered launches the next granule's words are requested
   // into `nxt` before the multiplications start.
   auto round_body = [&](int r, const Ring &cur, const uint32_t(&offc)[Q], const uint32_t(&entc)[Q], bool fastc, Ring &nxt,
-                        uint32_t(&offn)[Q], uint32_t(&entn)[Q], bool &fastn) {
+                        uint32_t(&offn)[Q], uint32_t(&entn)[Q], bool &fastn) __attribute__((always_inline)) {
     const int gi = gran0 + r * RG + rgi;
     const bool work = npw > 0 && gi < n_gran;
     const int h = gi & 1;
@@ -380,9 +383,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
         f_addr[p] = ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2);
         f_val[p] = 8u << (((v >> 2) & 7u) << 2);
       }
-#pragma unroll
+#pragma clang loop unroll(full)
       for (int pp = 0; pp < PMAX; ++pp) {
-        if (pp >= npw) break;  // uniform
+        if (pp < npw) {  // uniform (no break: the trip count stays a constant and the loop unrolls)
         const uint32_t mw = cur.mw[pp];
 #pragma unroll
         for (int p = 0; p < Q; ++p) {
@@ -450,6 +453,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
             default: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 3, sa, 0, 127); break;
           }
         }
+        }
       }
     }
     if constexpr (DB) {
@@ -511,7 +515,7 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
   for (int pw = PMAX; pw >= 1; --pw) {
     const int ks = (pairs + pw - 1) / pw;
     if (ks > kF4Waves) break;
-    const int rg = min(kF4Waves / ks, 8);  // at most 8 x 128 outputs per round: one per thread
+    const int rg = min(kF4Waves / ks, kF4Waves * 64 / 128);  // at most one output per thread and round
     const int wgs = (n_gran + rg - 1) / rg;
     const int grid = wgs < kSplitMaxGroups ? wgs : kSplitMaxGroups;
     const int rounds = (wgs + grid - 1) / grid;
@@ -553,7 +557,7 @@ bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ld
   if (x_dtype != XORENC_X_BF16 || D.J != 1) return false;
   if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
   // pairs per wave: what fits 128 registers with one set of compressed words; half of it with two sets
-  constexpr int PMAX = Q == 1 ? 8 : (Q == 2 ? 6 : (Q == 3 ? 4 : 3));
+  constexpr int PMAX = Q == 1 ? 8 : (Q == 2 ? 6 : (Q == 3 ? 4 : 2));
   constexpr int PMAX2 = (PMAX + 1) / 2;
   F4Plan P;
   if (!f4_plan(D, B, PMAX, &P)) return false;
