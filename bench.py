@@ -358,7 +358,7 @@ def marginal_rates(xe, torch, dev, args, wl, layer, base):
     compressed bytes, with the roofline fraction of each."""
     tall = tile_rows(layer, 4, xe, torch)
     res = {"workload": f"{wl.cfg.name} x4 rows: W {4 * wl.m}x{wl.n}", "batches": {}}
-    for B in (8, 64, 256):
+    for B in (1, 8, 64, 256):
         if B not in base:
             continue
         xg, _ = x_tensor(torch, wl, B, dev)

@@ -29,11 +29,12 @@
 // X-terms (A operand, M = 16): row 2 c + t is term t (0 = hi, 1 = lo) of column c, so the four D registers of a
 // lane are the hi and lo sums of two columns and are added in the lane.
 //
-// Work decomposition.  A workgroup converts X once (every wave needs it), then a wave keeps the operands of
-// its own K range (PW word pairs) in registers and walks over 16-row granules: per pair one mask dword, one
-// dword of encrypted bits per plane, one table look-up per table, four and-ors and one MFMA.  KS waves with
-// different K ranges share a granule; their partial sums meet in LDS in a fixed order.  All loads of a granule
-// are issued before anything else happens, so the stream is in flight while X is converted.
+// Work decomposition.  A workgroup converts X once (every wave needs it); a wave keeps the operands of its own
+// K range (PW word pairs) in registers and takes one 16-row granule: per pair one mask dword, one dword of
+// encrypted bits per plane, one table look-up per table, four and-ors and one MFMA.  KS waves with different K
+// ranges share a granule; their partial sums meet in LDS in a fixed order.  All loads of a granule are issued
+// before anything else happens, so the stream is in flight while X is converted.  The kernel is bound by the
+// number of instructions a SIMD has to issue (about 4.5 cycles each, measured), not by memory or the MFMA unit.
 #ifndef XORENC_SPMM_F4_H
 #define XORENC_SPMM_F4_H
 
@@ -52,16 +53,14 @@ constexpr int kF4MaxSpr = 256;              // 16 waves x 8 pairs x 2 words
 constexpr int kF4SclBytes = 2304;           // two scale bytes per (half-word, column)
 
 struct F4Plan {
-  int PW, KS, RG, grid, rounds;
+  int PW, KS, RG, grid;
 };
 
-// DB: the launch walks over more than one granule per wave: the next granule's words are requested while the
-// current one is multiplied (two register sets); otherwise one set.
 // kq_tab / rg_tab: four bits per wave, the wave's K range and its place among the RG granules of a round.
-template <int Q, int NIBT, int PMAX, bool DB>
+template <int Q, int NIBT, int PMAX>
 __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, const uint16_t *__restrict__ X, int64_t ldx,
                                                                int B, float *__restrict__ Y, int64_t ldy, int PW, int KS,
-                                                               int RG, int rounds, uint64_t kq_tab,
+                                                               int RG, uint64_t kq_tab,
                                                                uint64_t rg_tab) {
   constexpr int NT = kF4Waves * 64;
   constexpr bool two_dw = NIBT == 3;
@@ -80,7 +79,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   const int64_t l_n_slots = L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n), "s"(l_spr),
                "s"(l_nrb), "s"(l_n_units), "s"(l_q), "s"(n_in), "s"(l_n_slots), "s"(X), "s"(ldx), "s"(B), "s"(Y), "s"(ldy),
-               "s"(PW), "s"(KS), "s"(RG), "s"(rounds), "s"(kq_tab), "s"(rg_tab));
+               "s"(PW), "s"(KS), "s"(RG), "s"(kq_tab), "s"(rg_tab));
   __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -90,7 +89,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   const bool active = wave < KS * RG;
   const int n_gran = 2 * l_nrb;                       // granules of 16 rows
   const int w_lo = kq * 2 * PW;                       // first word of this wave's K range
-  const int gran0 = blockIdx.x * RG * rounds;         // the workgroup's granules are contiguous
+  const int gran0 = blockIdx.x * RG;                  // the workgroup's granules
   const int MB = 2 * B;                               // rows of the A operand in use
   const int spr64 = l_spr * 64;
   const uint32_t CS = (uint32_t)(spr64 * 2 + 16);     // bytes between the columns of the raw copy of X
@@ -146,34 +145,35 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     for (int p = 0; p < Q; ++p) e_base[p] = ((uint32_t)p * e_plane_units + u0) * e_unit_bytes;
 #pragma clang loop unroll(full)
     for (int pp = 0; pp < PMAX; ++pp) {
-      if (pp < npw) {  // uniform (no break: the trip count stays a constant and the loop unrolls)
-      R.mw[pp] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_voff + (uint32_t)(pp * 512), m_base, 0);
+      if (pp < npw) {  // uniform; a break here would make the trip count a run-time value and keep the loop rolled
+        R.mw[pp] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_voff + (uint32_t)(pp * 512), m_base, 0);
 #pragma unroll
-      for (int p = 0; p < Q; ++p) {
-        R.e0[pp][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, ev, e_base[p], 0);
-        if (two_dw) R.e1[pp][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, ev + 4u, e_base[p], 0);
-        e_base[p] += 2u * e_unit_bytes;
-      }
+        for (int p = 0; p < Q; ++p) {
+          R.e0[pp][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, ev, e_base[p], 0);
+          if (two_dw) R.e1[pp][p] = __builtin_amdgcn_raw_buffer_load_b32(ersrc, ev + 4u, e_base[p], 0);
+          e_base[p] += 2u * e_unit_bytes;
+        }
       }
     }
   };
-  // scales of the outputs this thread sums up at the end of a round (output o = tid, tid + NT)
+  // the compressed words of this wave's granule, and the scales of the output this thread sums up at the end
+  Ring ring;
+  uint32_t offv[Q];
+#pragma unroll
+  for (int p = 0; p < Q; ++p) offv[p] = 0u;
+  const int gi = gran0 + rgi;
+  const bool work = npw > 0 && gi < n_gran;
+  if (work) load_ring(gi, ring, offv);
   float al[Q];
-  auto load_alpha = [&](int r) {
-    const int go = gran0 + r * RG + (tid >> 7);
+  {
+    const int go = gran0 + (tid >> 7);
     const int row = (go >> 1) * 32 + (go & 1) * 16 + ((tid >> 3) & 15);
 #pragma unroll
     for (int p = 0; p < Q; ++p) {
       al[p] = 0.f;
       if (tid < RG * 128 && (tid & 7) < B && go < n_gran && row < l_m) al[p] = l_alpha[(int64_t)p * l_m + row];
     }
-  };
-  Ring ringA, ringB;  // ringB only lives in double-buffered launches
-  uint32_t offA[Q], offB[Q];
-#pragma unroll
-  for (int p = 0; p < Q; ++p) offA[p] = offB[p] = 0u;
-  if (npw > 0 && gran0 + rgi < n_gran) load_ring(gran0 + rgi, ringA, offA);
-  load_alpha(0);
+  }
 
   // ---- XOR tables in operand arrangement: T_b[v] = XOR of the columns 8b..8b+7 of M selected by the bits of v;
   // entry (b, v, half g), dword d: bit 4j+3 = bit 4j+d of half g of T_b[v]
@@ -306,20 +306,16 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
 
   // ---- patch entries of a granule's range: lane j holds the j-th entry (lists of more than 64 entries are
   // read from memory pair by pair instead); their offsets have arrived long ago
-  auto load_entries = [&](const uint32_t(&offv)[Q], uint32_t(&entv)[Q], bool &fast) __attribute__((always_inline)) {
-    fast = true;
+  uint32_t entv[Q];
+  bool fast = true;
 #pragma unroll
-    for (int p = 0; p < Q; ++p) {
-      const uint32_t base = __builtin_amdgcn_readlane(offv[p], 0);
-      const uint32_t total = __builtin_amdgcn_readlane(offv[p], 2 * PW) - base;  // lane 2 PW: end of the range
-      entv[p] = 0xFFFFu;
-      if (total > 64u) fast = false;
-      if ((uint32_t)lane < min(total, 64u)) entv[p] = (l_patch + base)[lane];
-    }
-  };
-  uint32_t entA[Q], entB[Q];
-  bool fastA = true, fastB = true;
-  load_entries(offA, entA, fastA);
+  for (int p = 0; p < Q; ++p) {
+    const uint32_t base = __builtin_amdgcn_readlane(offv[p], 0);
+    const uint32_t total = __builtin_amdgcn_readlane(offv[p], 2 * PW) - base;  // lane 2 PW: end of the range
+    entv[p] = 0xFFFFu;
+    if (total > 64u) fast = false;
+    if ((uint32_t)lane < min(total, 64u)) entv[p] = (l_patch + base)[lane];
+  }
   __syncthreads();  // operands and scales complete
 
   // ---- this wave's A operands: pair P = words w_lo + 2P (dwords 0..3) and w_lo + 2P + 1 (dwords 4..7).  Lanes
@@ -335,15 +331,15 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     const int wstep = 64 * MB;
 #pragma clang loop unroll(full)
     for (int pp = 0; pp < PMAX; ++pp) {
-      if (pp < npw) {  // uniform (no break: the trip count stays a constant and the loop unrolls)
-      const u32x4 c0 = *reinterpret_cast<const u32x4 *>(xsrc + (2 * pp) * wstep);
-      const u32x4 c1 = *reinterpret_cast<const u32x4 *>(xsrc + (2 * pp + 1) * wstep);
+      if (pp < npw) {  // uniform; a break here would make the trip count a run-time value and keep the loop rolled
+        const u32x4 c0 = *reinterpret_cast<const u32x4 *>(xsrc + (2 * pp) * wstep);
+        const u32x4 c1 = *reinterpret_cast<const u32x4 *>(xsrc + (2 * pp + 1) * wstep);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        xop[pp][i] = (int)c0[i];
-        xop[pp][4 + i] = (int)c1[i];
-      }
-      xsc[pp >> 2] |= (uint32_t)ssrc[pp * 4 * MB] << (8 * (pp & 3));
+        for (int i = 0; i < 4; ++i) {
+          xop[pp][i] = (int)c0[i];
+          xop[pp][4 + i] = (int)c1[i];
+        }
+        xsc[pp >> 2] |= (uint32_t)ssrc[pp * 4 * MB] << (8 * (pp & 3));
       }
     }
   }
@@ -355,21 +351,11 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   float *const red = reinterpret_cast<float *>(xs);
   __builtin_amdgcn_s_setprio(0);
 
-  // One granule: `cur` holds its words; in double-buffered launches the next granule's words are requested
-  // into `nxt` before the multiplications start.
-  auto round_body = [&](int r, const Ring &cur, const uint32_t(&offc)[Q], const uint32_t(&entc)[Q], bool fastc, Ring &nxt,
-                        uint32_t(&offn)[Q], uint32_t(&entn)[Q], bool &fastn) __attribute__((always_inline)) {
-    const int gi = gran0 + r * RG + rgi;
-    const bool work = npw > 0 && gi < n_gran;
-    const int h = gi & 1;
-    f32x4 acc[Q];
+  const int h = gi & 1;
+  f32x4 acc[Q];
 #pragma unroll
-    for (int p = 0; p < Q; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int gnext = gran0 + (r + 1) * RG + rgi;
-    const bool more = DB && r + 1 < rounds && npw > 0 && gnext < n_gran;
-    if constexpr (DB) {
-      if (more) load_ring(gnext, nxt, offn);
-    }
+  for (int p = 0; p < Q; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  {
     if (work) {
       const uint32_t sh = h ? e_sh1 : e_sh0;
       // per entry of the range (lane j = entry j = (row%32) << 6 | bit): where its flip goes inside the flip area of a
@@ -378,89 +364,86 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
       bool f_mine[Q];
 #pragma unroll
       for (int p = 0; p < Q; ++p) {
-        const uint32_t v = entc[p];
+        const uint32_t v = entv[p];
         f_mine[p] = (int)(v >> 10) == h;  // this granule holds rows 16h .. 16h+15 (an empty lane holds 0xFFFF)
         f_addr[p] = ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2);
         f_val[p] = 8u << (((v >> 2) & 7u) << 2);
       }
 #pragma clang loop unroll(full)
       for (int pp = 0; pp < PMAX; ++pp) {
-        if (pp < npw) {  // uniform (no break: the trip count stays a constant and the loop unrolls)
-        const uint32_t mw = cur.mw[pp];
+        if (pp < npw) {  // uniform; a break here would make the trip count a run-time value and keep the loop rolled
+          const uint32_t mw = ring.mw[pp];
 #pragma unroll
-        for (int p = 0; p < Q; ++p) {
-          uint32_t x;
-          if (two_dw)
-            x = __builtin_amdgcn_alignbit(cur.e1[pp][p], cur.e0[pp][p], sh);
-          else
-            x = cur.e0[pp][p] >> sh;
-          u32x4 sg;
-          {
-            const uint32_t i0 = NIBT == 1 ? __builtin_amdgcn_ubfe(x, 0, last_bits) : (x & 255u);
-            sg = *reinterpret_cast<const u32x4 *>(lut_lane + i0 * 32u);
-          }
-          if constexpr (NIBT >= 2) {
-            const uint32_t i1 = NIBT == 2 ? __builtin_amdgcn_ubfe(x, 8, last_bits) : ((x >> 8) & 255u);
-            sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 8192u + i1 * 32u);
-          }
-          if constexpr (NIBT >= 3) {
-            const uint32_t i2 = NIBT == 3 ? __builtin_amdgcn_ubfe(x, 16, last_bits) : ((x >> 16) & 255u);
-            sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 16384u + i2 * 32u);
-          }
-          if constexpr (NIBT >= 4) {
-            const uint32_t i3 = __builtin_amdgcn_ubfe(x, 24, last_bits);
-            sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 24576u + i3 * 32u);
-          }
-          // patch flips of the pair's two units: entries [pa, pb) of the list, the first unit's end at pm
-          const uint32_t base = __builtin_amdgcn_readlane(offc[p], 0);
-          const uint32_t pa = __builtin_amdgcn_readlane(offc[p], 2 * pp) - base;
-          const uint32_t pm = __builtin_amdgcn_readlane(offc[p], 2 * pp + 1) - base;
-          const uint32_t pb = __builtin_amdgcn_readlane(offc[p], 2 * pp + 2) - base;
-          if (pb > pa) {  // uniform
-            uint8_t *const fl = reinterpret_cast<uint8_t *>(myflips);
-            if (fastc) {
-              if (f_mine[p] && (uint32_t)lane >= pa && (uint32_t)lane < pb)
-                __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(fl + f_addr[p] + ((uint32_t)lane >= pm ? 512u : 0u)),
-                                       f_val[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-            } else {
-              for (uint32_t j0 = pa; j0 < pb; j0 += 64u) {  // uniform
-                const uint32_t j = j0 + (uint32_t)lane;
-                if (j < pb) {
-                  const uint32_t v = (l_patch + base)[j];
-                  if ((int)(v >> 10) == h)
-                    __hip_atomic_fetch_xor(
-                        reinterpret_cast<uint32_t *>(fl + ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2) +
-                                                     (j >= pm ? 512u : 0u)),
-                        8u << (((v >> 2) & 7u) << 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+          for (int p = 0; p < Q; ++p) {
+            uint32_t x;
+            if (two_dw)
+              x = __builtin_amdgcn_alignbit(ring.e1[pp][p], ring.e0[pp][p], sh);
+            else
+              x = ring.e0[pp][p] >> sh;
+            u32x4 sg;
+            {
+              const uint32_t i0 = NIBT == 1 ? __builtin_amdgcn_ubfe(x, 0, last_bits) : (x & 255u);
+              sg = *reinterpret_cast<const u32x4 *>(lut_lane + i0 * 32u);
+            }
+            if constexpr (NIBT >= 2) {
+              const uint32_t i1 = NIBT == 2 ? __builtin_amdgcn_ubfe(x, 8, last_bits) : ((x >> 8) & 255u);
+              sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 8192u + i1 * 32u);
+            }
+            if constexpr (NIBT >= 3) {
+              const uint32_t i2 = NIBT == 3 ? __builtin_amdgcn_ubfe(x, 16, last_bits) : ((x >> 16) & 255u);
+              sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 16384u + i2 * 32u);
+            }
+            if constexpr (NIBT >= 4) {
+              const uint32_t i3 = __builtin_amdgcn_ubfe(x, 24, last_bits);
+              sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 24576u + i3 * 32u);
+            }
+            // patch flips of the pair's two units: entries [pa, pb) of the list, the first unit's end at pm
+            const uint32_t base = __builtin_amdgcn_readlane(offv[p], 0);
+            const uint32_t pa = __builtin_amdgcn_readlane(offv[p], 2 * pp) - base;
+            const uint32_t pm = __builtin_amdgcn_readlane(offv[p], 2 * pp + 1) - base;
+            const uint32_t pb = __builtin_amdgcn_readlane(offv[p], 2 * pp + 2) - base;
+            if (pb > pa) {  // uniform
+              uint8_t *const fl = reinterpret_cast<uint8_t *>(myflips);
+              if (fast) {
+                if (f_mine[p] && (uint32_t)lane >= pa && (uint32_t)lane < pb)
+                  __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(fl + f_addr[p] + ((uint32_t)lane >= pm ? 512u : 0u)),
+                                         f_val[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+              } else {
+                for (uint32_t j0 = pa; j0 < pb; j0 += 64u) {  // uniform
+                  const uint32_t j = j0 + (uint32_t)lane;
+                  if (j < pb) {
+                    const uint32_t v = (l_patch + base)[j];
+                    if ((int)(v >> 10) == h)
+                      __hip_atomic_fetch_xor(
+                          reinterpret_cast<uint32_t *>(fl + ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2) +
+                                                       (j >= pm ? 512u : 0u)),
+                          8u << (((v >> 2) & 7u) << 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                  }
                 }
               }
+              u32x4 *fp = reinterpret_cast<u32x4 *>(fl + flip_lane);
+              sg ^= *fp;
+              *fp = u32x4{0u, 0u, 0u, 0u};
             }
-            u32x4 *fp = reinterpret_cast<u32x4 *>(fl + flip_lane);
-            sg ^= *fp;
-            *fp = u32x4{0u, 0u, 0u, 0u};
+            i32x8 bw;
+            bw[0] = (int)((mw & 0x11111111u) | sg[0]);
+            bw[1] = (int)((mw & 0x22222222u) | sg[1]);
+            bw[2] = (int)((mw & 0x44444444u) | sg[2]);
+            bw[3] = (int)(((mw >> 3) & 0x11111111u) | sg[3]);
+            bw[4] = bw[5] = bw[6] = bw[7] = 0;
+            const int sa = (int)xsc[pp >> 2];
+            switch (pp & 3) {  // the byte of the scale register is part of the instruction
+              case 0: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 0, sa, 0, 127); break;
+              case 1: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 1, sa, 0, 127); break;
+              case 2: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 2, sa, 0, 127); break;
+              default: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 3, sa, 0, 127); break;
+            }
           }
-          i32x8 bw;
-          bw[0] = (int)((mw & 0x11111111u) | sg[0]);
-          bw[1] = (int)((mw & 0x22222222u) | sg[1]);
-          bw[2] = (int)((mw & 0x44444444u) | sg[2]);
-          bw[3] = (int)(((mw >> 3) & 0x11111111u) | sg[3]);
-          bw[4] = bw[5] = bw[6] = bw[7] = 0;
-          const int sa = (int)xsc[pp >> 2];
-          switch (pp & 3) {  // the byte of the scale register is part of the instruction
-            case 0: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 0, sa, 0, 127); break;
-            case 1: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 1, sa, 0, 127); break;
-            case 2: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 2, sa, 0, 127); break;
-            default: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 3, sa, 0, 127); break;
-          }
-        }
         }
       }
     }
-    if constexpr (DB) {
-      if (more) load_entries(offn, entn, fastn);  // their offsets were requested before this granule's work
-    }
     // ---- partial sums of this wave: D rows 4q..4q+3 are (hi, lo) of columns 2q, 2q+1
-    float *const rbuf = red + (r & 1) * (kF4Waves * Q * 128);
+    float *const rbuf = red;
 #pragma unroll
     for (int p = 0; p < Q; ++p)
       *reinterpret_cast<float2 *>(rbuf + ((wave * Q + p) * 64 + lane) * 2) =
@@ -469,7 +452,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     // ---- every output sums the K ranges in ascending order, then the planes; -2 alpha: the codes are -t/2
     if (tid < RG * 128) {
       const int c = tid & 7, nrow = (tid >> 3) & 15, rg = tid >> 7;
-      const int go = gran0 + r * RG + rg;
+      const int go = gran0 + rg;
       const int row = (go >> 1) * 32 + (go & 1) * 16 + nrow;
       if (c < B && go < n_gran && row < l_m) {
         const float *src = rbuf + ((rg * KS) * Q * 64 + nrow + 16 * (c >> 1)) * 2 + (c & 1);
@@ -484,22 +467,12 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
         Y[(int64_t)row * ldy + c] = y;
       }
     }
-    if constexpr (DB) {
-      if (r + 1 < rounds) load_alpha(r + 1);
-    }
-  };
-  if constexpr (DB) {
-    for (int r = 0; r < rounds; r += 2) {  // uniform
-      round_body(r, ringA, offA, entA, fastA, ringB, offB, entB, fastB);
-      if (r + 1 < rounds) round_body(r + 1, ringB, offB, entB, fastB, ringA, offA, entA, fastA);
-    }
-  } else {
-    round_body(0, ringA, offA, entA, fastA, ringB, offB, entB, fastB);
   }
 }
 
-// Picks the decomposition: PW word pairs per wave (at most PMAX), KS K ranges, RG granules per workgroup at a
-// time; false when the kernel does not apply to the call.
+// Picks the decomposition: PW word pairs per wave (at most PMAX), KS K ranges, RG granules per workgroup; false
+// when the kernel does not apply to the call (a layer with more 16-row pieces than one round of workgroups takes
+// goes to the other kernels).
 inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
   if (B < 1 || B > kF4MaxB || D.J != 1 || D.spr > kF4MaxSpr) return false;
   const int spr_pad = 2 * ((D.spr + 1) / 2);  // whole word pairs
@@ -515,14 +488,13 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
   for (int pw = PMAX; pw >= 1; --pw) {
     const int ks = (pairs + pw - 1) / pw;
     if (ks > kF4Waves) break;
-    const int rg = min(kF4Waves / ks, kF4Waves * 64 / 128);  // at most one output per thread and round
+    const int rg = min(kF4Waves / ks, 8);  // at most 8 x 128 outputs per workgroup: one per thread
     const int wgs = (n_gran + rg - 1) / rg;
-    const int grid = wgs < kSplitMaxGroups ? wgs : kSplitMaxGroups;
-    const int rounds = (wgs + grid - 1) / grid;
-    const int cost = rounds * (pw + 2) * 1024 - grid;  // time of a wave; among equals, more workgroups
+    if (wgs > kSplitMaxGroups) continue;  // one workgroup per CU, one piece per wave
+    const int cost = (pw + 2) * 1024 - wgs;  // time of a wave; among equals, more workgroups
     if (cost < best_cost) {
       best_cost = cost;
-      best = F4Plan{pw, ks, rg, grid, rounds};
+      best = F4Plan{pw, ks, rg, wgs};
     }
   }
   if (best_cost == (1 << 30)) return false;
@@ -530,7 +502,7 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
   return true;
 }
 
-template <int Q, int PMAX, bool DB>
+template <int Q, int PMAX>
 int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, const F4Plan &P,
                   hipStream_t st) {
   const uint16_t *Xh = static_cast<const uint16_t *>(X);
@@ -541,10 +513,10 @@ int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y
     rg_tab |= (uint64_t)((w / P.KS) & 15) << (4 * w);
   }
   switch (D.nib) {
-    case 1: hipLaunchKernelGGL((spmm_f4_kernel<Q, 1, PMAX, DB>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
-    case 2: hipLaunchKernelGGL((spmm_f4_kernel<Q, 2, PMAX, DB>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
-    case 3: hipLaunchKernelGGL((spmm_f4_kernel<Q, 3, PMAX, DB>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
-    default: hipLaunchKernelGGL((spmm_f4_kernel<Q, 4, PMAX, DB>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
+    case 1: hipLaunchKernelGGL((spmm_f4_kernel<Q, 1, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
+    case 2: hipLaunchKernelGGL((spmm_f4_kernel<Q, 2, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
+    case 3: hipLaunchKernelGGL((spmm_f4_kernel<Q, 3, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
+    default: hipLaunchKernelGGL((spmm_f4_kernel<Q, 4, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
   }
   return xorenc_internal_check_launch();
 }
@@ -556,20 +528,11 @@ bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ld
                    hipStream_t st, int32_t *rc) {
   if (x_dtype != XORENC_X_BF16 || D.J != 1) return false;
   if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
-  // pairs per wave: what fits 128 registers with one set of compressed words; half of it with two sets
+  // pairs per wave: what fits 128 registers
   constexpr int PMAX = Q == 1 ? 8 : (Q == 2 ? 6 : (Q == 3 ? 4 : 2));
-  constexpr int PMAX2 = (PMAX + 1) / 2;
   F4Plan P;
   if (!f4_plan(D, B, PMAX, &P)) return false;
-  if (P.rounds == 1) {
-    *rc = launch_f4<Q, PMAX, false>(D, X, ldx, B, Y, ldy, P, st);
-  } else {
-    // several planes and only twice the pieces one round takes: the halved range per wave would double the rounds
-    // again, and the other kernels are as fast there
-    if (Q >= 2 && P.rounds == 2) return false;
-    if (!f4_plan(D, B, PMAX2, &P)) return false;
-    *rc = launch_f4<Q, PMAX2, true>(D, X, ldx, B, Y, ldy, P, st);
-  }
+  *rc = launch_f4<Q, PMAX>(D, X, ldx, B, Y, ldy, P, st);
   return true;
 }
 
