@@ -213,7 +213,7 @@ def kernel_source_digest():
     """Digest of the kernel sources: a traffic profile applies only to the sources it was taken with."""
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_1905_10138_amd", "csrc")
-    for name in ("xorenc_spmm_kernel.h", "xorenc_spmm_small.h", "xorenc_spmm.hip", "xorenc_device.h"):
+    for name in ("xorenc_spmm_kernel.h", "xorenc_spmm_small.h", "xorenc_spmm_f4.h", "xorenc_spmm.hip", "xorenc_device.h"):
         with open(os.path.join(src, name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
