@@ -80,6 +80,7 @@ namespace {
 // columns of a row.  A workgroup builds the tables once and walks over `chunks` runs of 256 slots.
 
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
 struct SlotStage {                       // phase-1 result of one slot, as phase 2 reads it
@@ -314,22 +315,43 @@ __global__ __launch_bounds__(256) void decode_kernel(DevLayer L, int out_kind, v
 }
 
 // ---------------------------------------------------------------------------------------------
-// Bit-plane output, slices of one 64-bit word: a leaner kernel of its own.  A wave takes one run of eight
-// consecutive word positions of one row block and never meets another wave after the tables are built: lane
-// (row rr = lane%32, h = lane/32) decodes words 4h .. 4h+3 of the run for its row, so its four results are 32
-// consecutive bytes of the row-major output and the two lanes of a row cover 64.  Everything the run needs is
-// requested before the tables are built; the patch entries of the whole run (one contiguous list) are fetched
+// Slices of one 64-bit word: a leaner kernel of its own for all three output kinds.  A wave takes one run of
+// eight consecutive word positions of one row block and never meets another wave after the tables are built:
+// lane (row rr = lane%32, h = lane/32) decodes words 4h .. 4h+3 of the run for its row.  Everything the run needs
+// is requested before the tables are built; the patch entries of the whole run (one contiguous list) are fetched
 // with one load, lane j = entry j, and scattered into a per-wave area of flip words that each lane then reads.
-template <int Q>
-__global__ __launch_bounds__(256) void decode_planes_kernel(DevLayer L, uint64_t *__restrict__ out, int runs_per_rb) {
-  __shared__ uint2 lut[4 * 256];             // T_b[v], b < nib
-  __shared__ uint64_t flips[4][Q][4][64];    // per wave: plane, word of the lane, lane
+//
+// Bit-plane output (KIND 0): the lane's four words are 32 consecutive bytes of the row-major output and the two
+// lanes of a row cover 64.
+//
+// Dense output (KIND 1 bf16, 2 fp32): the run is 512 columns of 32 rows.  The words go through a per-wave LDS
+// area (which the flip words no longer need), row by row; for row i lane l then takes byte l of the row's 64 bytes,
+// i.e. columns 8l .. 8l+7, so that one store instruction of the wave writes 1 KB (bf16) or two write 2 KB (fp32)
+// of consecutive addresses.  Expansion: the (sign, kept) pairs of the eight columns are laid out as eight FP4
+// (e2m1) codes s0k0 (kept -> 0010 = 1.0 or 1010 = -1.0, pruned -> 0000 = +0) through a 256-entry table that
+// spreads the bits of a byte over the nibbles of a dword; the hardware converts two codes to two floats per
+// instruction, and each plane is then one multiply (first plane) or one fused multiply-add by |alpha_p|, whose
+// product is exact: the same fp32 sums in the same order as ((+-a_1) + (+-a_2)) + ..., and +0.0 where pruned.
+template <int Q, int KIND>
+__global__ __launch_bounds__(256) void decode_run_kernel(DevLayer L, void *__restrict__ outv, int64_t ld,
+                                                         int runs_per_rb) {
+  constexpr bool DENSE = KIND != 0;
+  constexpr int RS = 80;  // bytes between staged rows: the 64 of the run and padding (spreads the staging writes over the banks)
+  constexpr int FLIP_BYTES = Q * 4 * 64 * 8;
+  constexpr int STAGE_BYTES = DENSE ? (1 + Q) * 32 * RS : 0;
+  constexpr int AREA = FLIP_BYTES > STAGE_BYTES ? FLIP_BYTES : STAGE_BYTES;
+  __shared__ uint2 lut[4 * 256];                                    // T_b[v], b < nib
+  __shared__ __attribute__((aligned(16))) uint8_t area_all[4][AREA];  // per wave: flip words, later the staged run
+  __shared__ uint32_t spread[DENSE ? 256 : 1];                      // bit e of the index -> bit 4e
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rr = lane & 31, h = lane >> 5;
   const int run = blockIdx.x * 4 + wave;
   const int rb = run / runs_per_rb, s_base = (run - rb * runs_per_rb) * 8;
   const bool live = rb < L.nrb;  // uniform per wave
   const int n_in = L.n_in, spr = L.spr;
+  const int r = rb * 32 + rr;
+  // flip words of the wave: [plane][word of the lane][lane]
+  uint64_t(*const flips)[4][64] = reinterpret_cast<uint64_t(*)[4][64]>(area_all[wave]);
   // ---- requests.  The nine patch offsets of the run (per plane) go first: loads return in order, and their
   // answer starts the only dependent request (the patch entries), which then travels with the bulk of the run.
   uint64_t keep[4];
@@ -353,6 +375,12 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(DevLayer L, uint64_t
       for (int p = 0; p < Q; ++p) x[p][i] = load_enc(L.enc, (int64_t)p * L.n_eslots + slot, n_in);
     }
   }
+  float al[Q];  // dense output: the scales of the lane's row
+#pragma unroll
+  for (int p = 0; p < Q; ++p) {
+    al[p] = 0.f;
+    if (DENSE && live && r < L.m) al[p] = L.alpha[(int64_t)p * L.m + r];
+  }
   // entries of the run's lists, lane j = entry j (the first 64; longer lists are read in further trips below)
   uint32_t ent[Q], ebase[Q], etotal[Q];
 #pragma unroll
@@ -373,10 +401,17 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(DevLayer L, uint64_t
     }
     lut[b * 256 + threadIdx.x] = make_uint2(lo, hi);
   }
+  if constexpr (DENSE) {
+    uint32_t v = threadIdx.x;
+    v = (v | (v << 12)) & 0x000F000Fu;
+    v = (v | (v << 6)) & 0x03030303u;
+    v = (v | (v << 3)) & 0x11111111u;
+    spread[threadIdx.x] = v;
+  }
 #pragma unroll
   for (int p = 0; p < Q; ++p)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) flips[wave][p][i][lane] = 0ull;
+    for (int i = 0; i < 4; ++i) flips[p][i][lane] = 0ull;
   __syncthreads();
   if (!live) return;
   // ---- patch entries -> flip words.  Entry j of the run's list belongs to word t = number of list ends <= j.
@@ -394,17 +429,16 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(DevLayer L, uint64_t
 #pragma unroll
         for (int k = 0; k < 7; ++k) t += j >= ends[k] ? 1u : 0u;
         // word t of the run is word t%4 of the lane (row, t/4)
-        atomicXor(reinterpret_cast<unsigned long long *>(&flips[wave][p][t & 3][(v >> 6) + 32u * (t >> 2)]),
+        atomicXor(reinterpret_cast<unsigned long long *>(&flips[p][t & 3][(v >> 6) + 32u * (t >> 2)]),
                   1ull << (v & 63u));
       }
     }
   }
-  // ---- decode, patch, mask; the lane's four words of a plane leave as 32 consecutive bytes
-  const int r = rb * 32 + rr;
+  // ---- decode, patch, mask
   const int s0 = s_base + 4 * h;
+  uint64_t w[Q][4];
 #pragma unroll
   for (int p = 0; p < Q; ++p) {
-    uint64_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       uint2 acc = lut[x[p][i] & 255u];
@@ -413,28 +447,149 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(DevLayer L, uint64_t
         acc.x ^= e.x;
         acc.y ^= e.y;
       }
-      w[i] = (((uint64_t)acc.y << 32 | acc.x) ^ flips[wave][p][i][lane]) & keep[i];
+      w[p][i] = (((uint64_t)acc.y << 32 | acc.x) ^ flips[p][i][lane]) & keep[i];
     }
-    if (r < L.m && s0 < spr) {
-      uint64_t *dst = out + ((int64_t)p * L.m + r) * spr + s0;
-      if (s0 + 3 < spr && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
-        *reinterpret_cast<ulonglong2 *>(dst) = make_ulonglong2(w[0], w[1]);
-        *reinterpret_cast<ulonglong2 *>(dst + 2) = make_ulonglong2(w[2], w[3]);
-      } else {
+    if constexpr (!DENSE) {  // the lane's four words of a plane leave as 32 consecutive bytes
+      if (r < L.m && s0 < spr) {
+        uint64_t *dst = static_cast<uint64_t *>(outv) + ((int64_t)p * L.m + r) * spr + s0;
+        if (s0 + 3 < spr && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+          *reinterpret_cast<ulonglong2 *>(dst) = make_ulonglong2(w[p][0], w[p][1]);
+          *reinterpret_cast<ulonglong2 *>(dst + 2) = make_ulonglong2(w[p][2], w[p][3]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (s0 + i < spr) dst[i] = w[i];
+          for (int i = 0; i < 4; ++i)
+            if (s0 + i < spr) dst[i] = w[p][i];
+        }
+      }
+    }
+  }
+  if constexpr (DENSE) {
+    // ---- the run through the wave's own LDS area: array a (0 = mask, 1 + p = plane p), row, byte of the run.
+    // The area held the flip words; this wave's reads of them are complete (a wave's LDS accesses are served in
+    // order) and no other wave touches the area.
+    uint8_t *const st = area_all[wave];
+    __builtin_amdgcn_wave_barrier();
+    auto put = [&](int a, const uint64_t(&v)[4]) {
+      uint4 *dst = reinterpret_cast<uint4 *>(st + (a * 32 + rr) * RS + 32 * h);
+      dst[0] = make_uint4((uint32_t)v[0], (uint32_t)(v[0] >> 32), (uint32_t)v[1], (uint32_t)(v[1] >> 32));
+      dst[1] = make_uint4((uint32_t)v[2], (uint32_t)(v[2] >> 32), (uint32_t)v[3], (uint32_t)(v[3] >> 32));
+    };
+    put(0, keep);
+#pragma unroll
+    for (int p = 0; p < Q; ++p) put(1 + p, w[p]);
+    __builtin_amdgcn_wave_barrier();
+    // A lane takes EPL consecutive columns per store: bf16 eight (byte `lane` of the row's 64, one store covers the
+    // 512 columns), fp32 four (half a byte; two passes of 256 columns), so that every store instruction of the wave
+    // writes 1 KB of consecutive addresses; such stores bypass the cache (nothing reads the lines again here).
+    constexpr int ESZ = KIND == 1 ? 2 : 4;
+    constexpr int EPL = KIND == 1 ? 8 : 4;
+    constexpr int NPASS = KIND == 1 ? 1 : 2;
+    const bool fast = (reinterpret_cast<uintptr_t>(outv) & 15) == 0 && ((ld * ESZ) & 15) == 0;  // uniform
+    const int rows = min(32, L.m - rb * 32);                                                    // uniform
+    const int64_t pitch = ld * ESZ;
+    uint32_t aabs[Q], aflip[Q];  // the lane's row: |alpha_p|, and 0xFF where alpha_p is negative (swaps the signs)
+#pragma unroll
+    for (int p = 0; p < Q; ++p) {
+      aabs[p] = __float_as_uint(al[p]) & 0x7fffffffu;
+      aflip[p] = (uint32_t)((int32_t)__float_as_uint(al[p]) >> 31) & 0xFFu;
+    }
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int bidx = KIND == 1 ? lane : 32 * pass + (lane >> 1);  // byte of the row's 64 this lane expands
+      const int cshift = KIND == 1 ? 0 : 16 * (lane & 1);           // its half of the byte's eight codes
+      const int col = s_base * 64 + 8 * bidx + (KIND == 1 ? 0 : 4 * (lane & 1));  // the lane's first column
+      const int nvalid = max(0, min(EPL, L.n - col));                             // its columns inside the matrix
+      uint8_t *const obase = static_cast<uint8_t *>(outv) + ((int64_t)rb * 32 * ld + col) * ESZ;
+      // the EPL values of row i for this lane
+      auto expand = [&](int i, float(&v)[EPL]) {
+        const uint32_t kb = st[i * RS + bidx];
+        const uint32_t ck = spread[kb] << 1;
+#pragma unroll
+        for (int p = 0; p < Q; ++p) {
+          const float aa = __uint_as_float(__builtin_amdgcn_readlane(aabs[p], i));  // |alpha_p| of row i
+          const uint32_t sf = __builtin_amdgcn_readlane(aflip[p], i);
+          const uint32_t wb = st[((1 + p) * 32 + i) * RS + bidx];
+          const uint32_t sb = ~(wb ^ sf) & kb;  // kept and bit 0: minus
+          const uint32_t code = ((spread[sb] << 3) | ck) >> cshift;
+          const f32x2_t f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 0);
+          const f32x2_t f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 1);
+          float f[8] = {f0[0], f0[1], f1[0], f1[1], 0.f, 0.f, 0.f, 0.f};
+          if constexpr (EPL == 8) {
+            const f32x2_t f2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 2);
+            const f32x2_t f3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(code, 1.0f, 3);
+            f[4] = f2[0], f[5] = f2[1], f[6] = f3[0], f[7] = f3[1];
+          }
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) v[e] = (p == 0) ? f[e] * aa : __builtin_fmaf(f[e], aa, v[e]);
+        }
+      };
+      auto pack_bf16 = [](const float(&v)[EPL], uint32_t(&pk)[4]) {
+#pragma unroll
+        for (int e = 0; e < EPL / 2; ++e) {
+          const f32x2_t two = {v[2 * e], v[2 * e + 1]};
+          pk[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));  // round to nearest even
+        }
+      };
+      if (fast && nvalid == EPL) {
+        // whole 16-byte pieces.  The loop has a fixed trip count (rows past the end of the matrix skip the store
+        // only), and four rows are expanded before their stores go out, so that their LDS reads overlap.
+        for (int i0 = 0; i0 < 32; i0 += 4) {
+          float v[4][EPL];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) expand(i0 + k, v[k]);
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (i0 + k < rows) {  // uniform
+              uint8_t *dst = obase + (i0 + k) * pitch;
+              if constexpr (KIND == 2) {
+                const f32x4_t q4 = {v[k][0], v[k][1], v[k][2], v[k][3]};
+                __builtin_nontemporal_store(q4, reinterpret_cast<f32x4_t *>(dst));
+              } else {
+                uint32_t pk[4];
+                pack_bf16(v[k], pk);
+                const u32x4 q4 = {pk[0], pk[1], pk[2], pk[3]};
+                __builtin_nontemporal_store(q4, reinterpret_cast<u32x4 *>(dst));
+              }
+            }
+        }
+      } else if (nvalid > 0) {  // ragged last columns, or rows of the output that are not 16-byte aligned
+        for (int i = 0; i < rows; ++i) {
+          float v[EPL];
+          expand(i, v);
+          uint8_t *dst = obase + i * pitch;
+          if constexpr (KIND == 2) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+              if (e < nvalid) reinterpret_cast<float *>(dst)[e] = v[e];
+          } else {
+            uint32_t pk[4];
+            pack_bf16(v, pk);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+              if (e < nvalid) reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)(pk[e >> 1] >> (16 * (e & 1)));
+          }
+        }
       }
     }
   }
 }
 
-template <int Q>
-void launch_decode_planes(const DevLayer &D, void *out, hipStream_t st) {
+template <int Q, int KIND>
+void launch_decode_run(const DevLayer &D, void *out, int64_t ld, hipStream_t st) {
   const int runs_per_rb = (D.spr + 7) / 8;
   const int64_t runs = (int64_t)runs_per_rb * D.nrb;
-  hipLaunchKernelGGL(decode_planes_kernel<Q>, dim3((unsigned)((runs + 3) / 4)), dim3(256), 0, st, D,
-                     static_cast<uint64_t *>(out), runs_per_rb);
+  hipLaunchKernelGGL((decode_run_kernel<Q, KIND>), dim3((unsigned)((runs + 3) / 4)), dim3(256), 0, st, D, out, ld,
+                     runs_per_rb);
+}
+
+template <int KIND>
+void launch_decode_run_q(const DevLayer &D, void *out, int64_t ld, hipStream_t st) {
+  switch (D.q) {
+    case 1: launch_decode_run<1, KIND>(D, out, ld, st); break;
+    case 2: launch_decode_run<2, KIND>(D, out, ld, st); break;
+    case 3: launch_decode_run<3, KIND>(D, out, ld, st); break;
+    default: launch_decode_run<4, KIND>(D, out, ld, st); break;
+  }
 }
 
 }  // namespace
@@ -454,14 +609,15 @@ int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, void *out, in
   const uintptr_t al = out_kind == XORENC_OUT_PLANES ? 7 : (out_kind == XORENC_OUT_F32 ? 3 : 1);
   if ((uintptr_t)out & al) return XORENC_EALIGN;
   xorenc_internal_begin_call();
-  if (out_kind == XORENC_OUT_PLANES && D.J == 1 && (int64_t)((D.spr + 7) / 8) * D.nrb < ((int64_t)1 << 32)) {
+  // slices of one word: one wave per run of eight word positions, for every output kind
+  if (D.J == 1 && (int64_t)((D.spr + 7) / 8) * D.nrb < ((int64_t)1 << 32)) {
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    switch (D.q) {
-      case 1: launch_decode_planes<1>(D, out, st); break;
-      case 2: launch_decode_planes<2>(D, out, st); break;
-      case 3: launch_decode_planes<3>(D, out, st); break;
-      default: launch_decode_planes<4>(D, out, st); break;
-    }
+    if (out_kind == XORENC_OUT_PLANES)
+      launch_decode_run_q<0>(D, out, ld_out, st);
+    else if (out_kind == XORENC_OUT_BF16)
+      launch_decode_run_q<1>(D, out, ld_out, st);
+    else
+      launch_decode_run_q<2>(D, out, ld_out, st);
     return xorenc_internal_check_launch();
   }
   // A workgroup takes `chunks` runs of eight word positions of one row block: a couple of thousand workgroups

@@ -152,3 +152,26 @@ def test_dense_decode_sums_three_planes_left_to_right():
     assert np.abs(want).max() == np.float32(1.0)       # never 1 + 2^-23, which the other order would give
     got16 = xe.decode(L, xe.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
     assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(want))
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in", [("lstm", 130, 3000, 64, 8), ("large_q2", 96, 1100, 64, 12),
+                                                 ("lstm", 70, 900, 128, 16)])
+def test_dense_decode_with_negative_and_zero_scales(name, m, n, n_out, n_in):
+    """Scales of either sign and exact zeros (a zero scale gives -0.0 where the bit is 0, +0.0 where it is 1 or the
+    weight is pruned): dense outputs stay bit-identical to the oracle for one-word and multi-word slices."""
+    import copy
+    import torch
+    import paper_1905_10138_amd as xe
+    wl, enc0 = encoded_workload(name, m, n, n_out=n_out, n_in=n_in)
+    enc = copy.copy(enc0)
+    rng = np.random.default_rng(123)
+    a = np.array(enc.alpha, dtype=np.float32, copy=True)
+    a *= rng.choice(np.array([1.0, -1.0, 1.0, 0.0], np.float32), size=a.shape)
+    enc.alpha = a
+    assert (a < 0).any() and (a == 0).any() and (a > 0).any()
+    L = pack_encoded(enc).to(torch.device("cuda:0"))
+    want = decoder.dequantize_f32(enc)
+    got = xe.decode(L, xe.OUT_F32).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    got16 = xe.decode(L, xe.OUT_BF16).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got16, decoder.round_f32_to_bf16_bits(want))
