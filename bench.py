@@ -420,15 +420,16 @@ def storage_extra(xe, layer):
 
 def encoder_extra(xe, torch, dev, base_cfg):
     """Both GPU encoders (Algorithm 1; the 2^n_in search of Section 5.2) on the default matrix, at its own
-    slice geometry and at n_out = 128 / n_in = 16.  Times are host wall-clock around the binding call
+    slice geometry, at n_out = 128 / n_in = 16 and at the paper's preferred n_out = 192 / n_in = 20 (Section 3.3:
+    2^20 inputs per slice).  Times are host wall-clock around the binding call
     (buffer allocation, the kernels, one synchronisation to read the patch total), best of three."""
     import dataclasses
 
     from synth_inputs import make_workload
     res = []
-    for n_out, n_in in ((base_cfg.n_out, base_cfg.n_in), (128, 16)):
+    for n_out, n_in in ((base_cfg.n_out, base_cfg.n_in), (128, 16), (192, 20)):
         cfg = dataclasses.replace(base_cfg, n_out=n_out, n_in=n_in)
-        if n_in > 16:
+        if n_in > 24:
             continue
         wl = make_workload(cfg)
         mask, planes, alpha, M_rows = encoder_inputs(wl, xe, torch, dev)

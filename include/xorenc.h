@@ -225,10 +225,12 @@ XORENC_API int32_t xorenc_encode(int32_t m, int32_t n, int32_t n_in, int32_t q, 
  * every slice all 2^n_in inputs of the XOR-gate network are tried and one whose output differs from
  * the quantised bits on the fewest care positions is kept; among equals the smallest input read as
  * an integer (bit j = x_j).  Patches are the remaining mismatches.  Arguments, outputs, workspace and
- * stream behaviour exactly as xorenc_encode.  Work is l * 2^n_in per plane: XORENC_EUNSUPPORTED for
+ * stream behaviour exactly as xorenc_encode.  Work is l * 2^n_in network evaluations per plane, one slice per
+ * lane and all of a slice's inputs in one kernel (about 3 * 10^12 evaluations per second on one MI355X: a million
+ * slices take 20 ms at n_in = 16 and several seconds at n_in = 24): XORENC_EUNSUPPORTED for
  * n_in > XORENC_EXH_MAX_N_IN.
  */
-#define XORENC_EXH_MAX_N_IN 16
+#define XORENC_EXH_MAX_N_IN 24
 XORENC_API int32_t xorenc_encode_exhaustive(int32_t m, int32_t n, int32_t n_in, int32_t q, int32_t n_out,
                                             const uint32_t *M_rows, const uint64_t *mask, const uint64_t *planes,
                                             uint8_t *enc_out, uint32_t *patch_off_out, uint16_t *patch_out,

@@ -88,3 +88,30 @@ def exhaustive_min_patches(care: np.ndarray, bits: np.ndarray, M: np.ndarray):
     dist = (ys[:, idx] != target).sum(axis=1)
     best = int(dist.argmin())
     return int(dist[best]), xs[best]
+
+
+def exhaustive_min_patches_in_parts(care: np.ndarray, bits: np.ndarray, M: np.ndarray, part_bits: int = 16):
+    """Section 5.2 for wider inputs (the paper calls n_in below 30 practical): the same listing of all 2^n_in
+    inputs, taken 2^part_bits inputs at a time so that it fits in memory.  Returns (fewest mismatched care bits,
+    the smallest input, read as an integer with bit j = x_j, that attains it, as a bit vector).
+
+    The parts are visited in ascending order of the inputs and a later part replaces the best so far only when
+    it is strictly better, so that among equally good inputs the smallest integer wins, as in the one-part listing.
+    """
+    M = np.asarray(M, dtype=np.uint8)
+    n_out, n_in = M.shape
+    part_bits = min(part_bits, n_in)
+    idx = np.flatnonzero(care)
+    target = np.asarray(bits, dtype=np.uint8)[idx]
+    low = np.arange(1 << part_bits, dtype=np.int64)
+    best_dist, best_x = None, None
+    for high in range(1 << (n_in - part_bits)):
+        ints = low + (high << part_bits)
+        xs = ((ints[:, None] >> np.arange(n_in)) & 1).astype(np.uint8)
+        ys = xor_network(M, xs)
+        dist = (ys[:, idx] != target).sum(axis=1)
+        k = int(dist.argmin())                      # first minimum of the part = its smallest input
+        if best_dist is None or int(dist[k]) < best_dist:
+            best_dist, best_x = int(dist[k]), xs[k]
+    return best_dist, best_x
+

@@ -15,6 +15,7 @@
 // is wave-uniform and is kept up to date with one XOR of a column of M per step; a lane only counts
 // the mismatches on its own slice.  Ties go to the smallest input read as an integer.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include <mutex>
 
@@ -133,7 +134,8 @@ struct ExhParams {
   uint64_t Mcol[XORENC_MAX_J][XORENC_EXH_MAX_N_IN];  // [w][j]: bit i = M[64 w + i][j]
 };
 
-template <int J>
+// WIDE: more than 16 input bits, where the pair (mismatches, input) no longer fits one 32-bit word.
+template <int J, bool WIDE>
 __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParams P) {
   const int tid = threadIdx.x;
   const int64_t gid = (int64_t)blockIdx.x * ENC_THREADS + tid;
@@ -163,7 +165,8 @@ __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParam
     c1[w] = P.Mcol[w][1];
     c2[w] = P.Mcol[w][2];
   }
-  uint32_t best = 0xffffffffu;  // (mismatches << 16) | x: the minimum is the fewest patches, then the smallest x
+  // (mismatches << 16) | x, or (mismatches << 32) | x: the minimum is the fewest patches, then the smallest x
+  typename std::conditional<WIDE, uint64_t, uint32_t>::type best = WIDE ? ~0ull : 0xffffffffu;
   auto flip = [&](int j, const uint64_t(&col)[J]) {
     x ^= 1u << j;
 #pragma unroll
@@ -173,7 +176,12 @@ __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParam
     uint32_t cnt = 0;
 #pragma unroll
     for (int w = 0; w < J; ++w) cnt += (uint32_t)__builtin_popcountll((y[w] & care[w]) ^ want[w]);
-    best = min(best, (cnt << 16) | x);
+    if constexpr (WIDE) {
+      const uint64_t key = ((uint64_t)cnt << 32) | x;
+      best = key < best ? key : best;
+    } else {
+      best = min(best, (cnt << 16) | x);
+    }
   };
   // Gray code walk: step k flips bit ctz(k); inside a group of 8 steps the flipped bits are
   // 0 1 0 2 0 1 0, and only the step into the next group needs a column chosen at run time.
@@ -195,7 +203,7 @@ __global__ __launch_bounds__(ENC_THREADS) void exhaustive_slices_kernel(ExhParam
     flip(1, c1); eval();
     flip(0, c0); eval();
   }
-  const uint32_t xb = best & 0xffffu;
+  const uint32_t xb = WIDE ? (uint32_t)best : (uint32_t)best & 0xffffu;
   // output of the chosen input, patches = mismatched care bits
 #pragma unroll
   for (int w = 0; w < J; ++w) {
@@ -377,11 +385,21 @@ int32_t encode_common(bool exhaustive, int32_t m, int32_t n, int32_t n_in, int32
           for (int i = 0; i < 64; ++i) col |= (uint64_t)((M_rows[64 * w + i] >> j) & 1u) << i;
         P.Mcol[w][j] = col;
       }
-    switch (J) {
-      case 1: hipLaunchKernelGGL(exhaustive_slices_kernel<1>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
-      case 2: hipLaunchKernelGGL(exhaustive_slices_kernel<2>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
-      case 3: hipLaunchKernelGGL(exhaustive_slices_kernel<3>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
-      default: hipLaunchKernelGGL(exhaustive_slices_kernel<4>, dim3(eblocks), dim3(ENC_THREADS), 0, st, P); break;
+    const dim3 eg(eblocks), eb(ENC_THREADS);
+    if (n_in <= 16) {
+      switch (J) {
+        case 1: hipLaunchKernelGGL((exhaustive_slices_kernel<1, false>), eg, eb, 0, st, P); break;
+        case 2: hipLaunchKernelGGL((exhaustive_slices_kernel<2, false>), eg, eb, 0, st, P); break;
+        case 3: hipLaunchKernelGGL((exhaustive_slices_kernel<3, false>), eg, eb, 0, st, P); break;
+        default: hipLaunchKernelGGL((exhaustive_slices_kernel<4, false>), eg, eb, 0, st, P); break;
+      }
+    } else {
+      switch (J) {
+        case 1: hipLaunchKernelGGL((exhaustive_slices_kernel<1, true>), eg, eb, 0, st, P); break;
+        case 2: hipLaunchKernelGGL((exhaustive_slices_kernel<2, true>), eg, eb, 0, st, P); break;
+        case 3: hipLaunchKernelGGL((exhaustive_slices_kernel<3, true>), eg, eb, 0, st, P); break;
+        default: hipLaunchKernelGGL((exhaustive_slices_kernel<4, true>), eg, eb, 0, st, P); break;
+      }
     }
   } else {
     EncParams P;

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from helpers import encoded_workload, paper_format_arrays
-from oracle import decoder
+from oracle import decoder, gf2
 
 pytestmark = pytest.mark.gpu
 
@@ -96,10 +96,59 @@ def test_gpu_exhaustive_encoder_random_geometries(name, m, n, n_out, n_in, S):
 def test_exhaustive_encoder_rejects_large_n_in():
     import torch
     import paper_1905_10138_amd as xe
-    wl, _ = encoded_workload("tiny", 33, 70, n_out=128, n_in=24)
+    wl, _ = encoded_workload("tiny", 33, 70, n_out=128, n_in=25)
     with pytest.raises(xe.XorencError):
         gpu_encode(wl, exhaustive=True)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,m,n,n_out,n_in,S,sample", [("lstm", 40, 700, 64, 18, 0.7, 10),
+                                                          ("large_q2", 24, 500, 128, 20, 0.85, 6),
+                                                          ("tiny", 33, 70, 192, 22, 0.7, 3),
+                                                          ("fig1", 20, 130, 64, 24, 0.6, 3)])
+def test_gpu_exhaustive_encoder_wide_inputs_on_sampled_slices(name, m, n, n_out, n_in, S, sample):
+    """Section 5.2 beyond 16 input bits (the paper calls n_in below 30 practical).  The oracle lists the 2^n_in
+    inputs of a slice in parts, which takes seconds per slice, so a seeded sample of slices is compared bit for
+    bit (w^c, n_patch, d_patch); every slice is checked for what holds at any size: the patched output reproduces
+    all kept bits (lossless round trip through the GPU decoder), the stored patches are exactly the mismatches of
+    the stored input, and no slice has more patches than Algorithm 1 gives it."""
+    import paper_1905_10138_amd as xe
+    from oracle import patch_search
+    wl, alg1 = encoded_workload(name, m, n, S=S, n_out=n_out, n_in=n_in)      # the oracle's Algorithm 1 encoding
+    L = gpu_encode(wl, exhaustive=True)
+    host = L.to_host()
+    assert xe.check_packed(host) == 0
+    w_c, keep, n_patch, d_patch = xe.unpack(host)
+    ow, ok, onp, odp, _ = paper_format_arrays(alg1)
+    assert np.array_equal(keep, ok)
+    assert np.all(n_patch <= onp)
+    planes = xe.decode(L, xe.OUT_PLANES).cpu().numpy().view(np.uint64)
+    assert np.array_equal(planes, decoder.pack_planes_u64(wl.planes))
+    # per slice: care set, wanted bits, the GPU's input bits and patch positions
+    q, l = alg1.n_patch.shape
+    care = wl.keep.reshape(l, n_out)
+    bits = wl.planes.reshape(q, l, n_out)
+    x_bits = ((np.asarray(w_c, dtype=np.uint64).reshape(q, l)[..., None] >> np.arange(n_in, dtype=np.uint64)) & 1).astype(np.uint8)
+    counts = np.asarray(n_patch).reshape(q, l).astype(np.int64)
+    starts = np.concatenate([np.zeros((q, 1), np.int64), np.cumsum(counts, axis=1)], axis=1)
+    flat = np.asarray(d_patch)
+    plane_base = np.concatenate([np.zeros(1, np.int64), np.cumsum(counts.sum(axis=1))])
+    def patches_of(p, s):
+        return flat[plane_base[p] + starts[p, s]:plane_base[p] + starts[p, s + 1]]
+    for p in range(q):
+        y = gf2.xor_network(wl.M, x_bits[p]).astype(bool)                     # every slice's raw output
+        mism = (y != bits[p]) & care
+        assert np.array_equal(mism.sum(axis=1), counts[p])
+    rng = np.random.default_rng(n_in)
+    busy = np.flatnonzero(care.sum(axis=1) > n_in // 2)                       # slices where the search has work to do
+    picks = rng.choice(busy if busy.size >= sample else np.arange(l), size=sample, replace=False)
+    for s in picks:
+        p = int(rng.integers(q))
+        opt, x_opt = patch_search.exhaustive_min_patches_in_parts(care[s], bits[p, s], wl.M, 18)
+        assert counts[p, s] == opt
+        assert np.array_equal(x_bits[p, s], x_opt)
+        y = gf2.xor_network(wl.M, x_opt[None])[0].astype(bool)
+        assert np.array_equal(np.sort(patches_of(p, s)), np.flatnonzero((y != bits[p, s]) & care[s]))
 
 
 @pytest.mark.parametrize("name,m,n", CASES)

@@ -230,3 +230,45 @@ def test_vectorised_exhaustive_search_against_the_per_slice_listing(n_out, n_in,
         y = gf2.xor_network(M, w_c[s][None])[0].astype(bool)
         y[pos[s]] ^= True
         assert np.array_equal(y & care[s], bits[s])
+
+
+@pytest.mark.parametrize("n_out,n_in,part_bits,p_care", [(64, 10, 4, 0.15), (128, 12, 7, 0.1), (64, 9, 16, 0.3),
+                                                         (192, 11, 1, 0.05)])
+def test_exhaustive_listing_in_parts_equals_the_one_part_listing(n_out, n_in, part_bits, p_care):
+    """The listing taken 2^part_bits inputs at a time (Section 5.2 for wider inputs) returns the same minimum and
+    the same smallest input as the listing taken at once, whatever the part size."""
+    rng = np.random.default_rng(100 * n_out + n_in)
+    M = rng.integers(0, 2, size=(n_out, n_in), dtype=np.uint8)
+    for _ in range(12):
+        care = rng.random(n_out) < p_care
+        bits = rng.integers(0, 2, size=n_out).astype(np.uint8) & care
+        d0, x0 = patch_search.exhaustive_min_patches(care, bits, M)
+        d1, x1 = patch_search.exhaustive_min_patches_in_parts(care, bits, M, part_bits)
+        assert d0 == d1
+        assert np.array_equal(x0, x1)
+
+
+def test_exhaustive_listing_in_parts_on_planted_inputs_of_18_bits():
+    """n_in = 18, where the one-part listing is already heavy.  The outputs of a planted input with up to two care
+    bits turned over: the minimum is at most the number turned over; the network has full column rank on the
+    care set, so with nothing turned over the planted input is the only one with zero mismatches and is returned;
+    and ties go to the smallest integer: with a zero column in M the bit of that column comes back 0."""
+    rng = np.random.default_rng(18)
+    n_out, n_in = 64, 18
+    M = rng.integers(0, 2, size=(n_out, n_in), dtype=np.uint8)
+    care = np.ones(n_out, dtype=bool)                              # 64 equations, 18 unknowns
+    reduced = patch_search.row_reduce(np.concatenate([M, np.zeros((n_out, 1), np.uint8)], axis=1))
+    assert int(reduced[:, :-1].any(axis=1).sum()) == n_in          # full column rank over GF(2): one solution at most
+    x = rng.integers(0, 2, size=n_in, dtype=np.uint8)
+    y = gf2.xor_network(M, x[None])[0]
+    d, xb = patch_search.exhaustive_min_patches_in_parts(care, y, M, 14)
+    assert d == 0 and np.array_equal(xb, x)
+    y2 = y.copy(); y2[[5, 40]] ^= 1
+    d2, xb2 = patch_search.exhaustive_min_patches_in_parts(care, y2, M, 14)
+    assert d2 <= 2
+    assert int((gf2.xor_network(M, xb2[None])[0] != y2).sum()) == d2
+    M0 = M.copy(); M0[:, 17] = 0                                   # input bit 17 changes nothing
+    x17 = x.copy(); x17[17] = 1
+    y0 = gf2.xor_network(M0, x17[None])[0]
+    d3, xb3 = patch_search.exhaustive_min_patches_in_parts(care, y0, M0, 14)
+    assert d3 == 0 and xb3[17] == 0
