@@ -53,14 +53,18 @@ constexpr int kF4MaxSpr = 256;              // 16 waves x 8 pairs x 2 words
 constexpr int kF4SclBytes = 2304;           // two scale bytes per (half-word, column)
 
 struct F4Plan {
-  int PW, KS, RG, grid;
+  int PW, KS, RG, grid, rounds;
 };
 
 // kq_tab / rg_tab: four bits per wave, the wave's K range and its place among the RG granules of a round.
-template <int Q, int NIBT, int PMAX>
+// MR: a workgroup walks over `rounds` sets of RG granules (layers with more granules than one round of workgroups
+// takes).  X is converted and the tables are built once; the compressed words, patch offsets and scales of the next
+// round are requested before the current round's work (always the same number of requests, granule indices
+// clamped to the last one, so that the waits can count them), its patch entries after it.
+template <int Q, int NIBT, int PMAX, bool MR>
 __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, const uint16_t *__restrict__ X, int64_t ldx,
                                                                int B, float *__restrict__ Y, int64_t ldy, int PW, int KS,
-                                                               int RG, uint64_t kq_tab,
+                                                               int RG, int rounds, uint64_t kq_tab,
                                                                uint64_t rg_tab) {
   constexpr int NT = kF4Waves * 64;
   constexpr bool two_dw = NIBT == 3;
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   const int64_t l_n_slots = L.n_slots;
   asm volatile("" ::"s"(l_enc), "s"(l_mask32), "s"(l_patch_off), "s"(l_patch), "s"(l_alpha), "s"(l_m), "s"(l_n), "s"(l_spr),
                "s"(l_nrb), "s"(l_n_units), "s"(l_q), "s"(n_in), "s"(l_n_slots), "s"(X), "s"(ldx), "s"(B), "s"(Y), "s"(ldy),
-               "s"(PW), "s"(KS), "s"(RG), "s"(kq_tab), "s"(rg_tab));
+               "s"(PW), "s"(KS), "s"(RG), "s"(rounds), "s"(kq_tab), "s"(rg_tab));
   __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   const bool active = wave < KS * RG;
   const int n_gran = 2 * l_nrb;                       // granules of 16 rows
   const int w_lo = kq * 2 * PW;                       // first word of this wave's K range
-  const int gran0 = blockIdx.x * RG;                  // the workgroup's granules
+  const int gran0 = blockIdx.x * RG * (MR ? rounds : 1);  // the workgroup's granules are contiguous
   const int MB = 2 * B;                               // rows of the A operand in use
   const int spr64 = l_spr * 64;
   const uint32_t CS = (uint32_t)(spr64 * 2 + 16);     // bytes between the columns of the raw copy of X
@@ -145,7 +149,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     for (int p = 0; p < Q; ++p) e_base[p] = ((uint32_t)p * e_plane_units + u0) * e_unit_bytes;
 #pragma clang loop unroll(full)
     for (int pp = 0; pp < PMAX; ++pp) {
-      if (pp < npw) {  // uniform; a break here would make the trip count a run-time value and keep the loop rolled
+      // uniform; a break here would make the trip count a run-time value and keep the loop rolled.  With several
+      // rounds every pair is requested (beyond the row or the arrays the descriptor's range check returns zero).
+      if (MR || pp < npw) {
         R.mw[pp] = __builtin_amdgcn_raw_buffer_load_b32(mrsrc, m_voff + (uint32_t)(pp * 512), m_base, 0);
 #pragma unroll
         for (int p = 0; p < Q; ++p) {
@@ -161,19 +167,18 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   uint32_t offv[Q];
 #pragma unroll
   for (int p = 0; p < Q; ++p) offv[p] = 0u;
-  const int gi = gran0 + rgi;
-  const bool work = npw > 0 && gi < n_gran;
-  if (work) load_ring(gi, ring, offv);
+  if (MR || (npw > 0 && gran0 + rgi < n_gran)) load_ring(min(gran0 + rgi, n_gran - 1), ring, offv);
   float al[Q];
-  {
-    const int go = gran0 + (tid >> 7);
+  auto load_alpha = [&](int r, float(&a)[Q]) __attribute__((always_inline)) {
+    const int go = min(gran0 + r * RG + (tid >> 7), n_gran - 1);
     const int row = (go >> 1) * 32 + (go & 1) * 16 + ((tid >> 3) & 15);
 #pragma unroll
     for (int p = 0; p < Q; ++p) {
-      al[p] = 0.f;
-      if (tid < RG * 128 && (tid & 7) < B && go < n_gran && row < l_m) al[p] = l_alpha[(int64_t)p * l_m + row];
+      a[p] = 0.f;
+      if (tid < RG * 128 && (tid & 7) < B && row < l_m) a[p] = l_alpha[(int64_t)p * l_m + row];
     }
-  }
+  };
+  load_alpha(0, al);
 
   // ---- XOR tables in operand arrangement: T_b[v] = XOR of the columns 8b..8b+7 of M selected by the bits of v;
   // entry (b, v, half g), dword d: bit 4j+3 = bit 4j+d of half g of T_b[v]
@@ -308,14 +313,18 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   // read from memory pair by pair instead); their offsets have arrived long ago
   uint32_t entv[Q];
   bool fast = true;
+  auto load_entries = [&](const uint32_t(&off)[Q], uint32_t(&ent)[Q], bool &fst) __attribute__((always_inline)) {
+    fst = true;
 #pragma unroll
-  for (int p = 0; p < Q; ++p) {
-    const uint32_t base = __builtin_amdgcn_readlane(offv[p], 0);
-    const uint32_t total = __builtin_amdgcn_readlane(offv[p], 2 * PW) - base;  // lane 2 PW: end of the range
-    entv[p] = 0xFFFFu;
-    if (total > 64u) fast = false;
-    if ((uint32_t)lane < min(total, 64u)) entv[p] = (l_patch + base)[lane];
-  }
+    for (int p = 0; p < Q; ++p) {
+      const uint32_t base = __builtin_amdgcn_readlane(off[p], 0);
+      const uint32_t total = __builtin_amdgcn_readlane(off[p], 2 * PW) - base;  // lane 2 PW: end of the range
+      ent[p] = 0xFFFFu;
+      if (total > 64u) fst = false;
+      if ((uint32_t)lane < min(total, 64u)) ent[p] = (l_patch + base)[lane];
+    }
+  };
+  load_entries(offv, entv, fast);
   __syncthreads();  // operands and scales complete
 
   // ---- this wave's A operands: pair P = words w_lo + 2P (dwords 0..3) and w_lo + 2P + 1 (dwords 4..7).  Lanes
@@ -351,11 +360,15 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   float *const red = reinterpret_cast<float *>(xs);
   __builtin_amdgcn_s_setprio(0);
 
-  const int h = gi & 1;
-  f32x4 acc[Q];
+  // one round: the granules gran0 + r RG .. of the workgroup
+  auto round_body = [&](int r, const Ring &ring, const uint32_t(&offv)[Q], const uint32_t(&entv)[Q], bool fast,
+                        const float(&al)[Q], auto &&between) __attribute__((always_inline)) {
+    const int gi = gran0 + r * RG + rgi;
+    const bool work = npw > 0 && gi < n_gran;
+    const int h = gi & 1;
+    f32x4 acc[Q];
 #pragma unroll
-  for (int p = 0; p < Q; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-  {
+    for (int p = 0; p < Q; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (work) {
       const uint32_t sh = h ? e_sh1 : e_sh0;
       // per entry of the range (lane j = entry j = (row%32) << 6 | bit): where its flip goes inside the flip area of a
@@ -442,8 +455,10 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
         }
       }
     }
-    // ---- partial sums of this wave: D rows 4q..4q+3 are (hi, lo) of columns 2q, 2q+1
-    float *const rbuf = red;
+    between();
+    // ---- partial sums of this wave: D rows 4q..4q+3 are (hi, lo) of columns 2q, 2q+1 (two areas in turn, so that
+    // one barrier per round is enough)
+    float *const rbuf = red + (r & 1) * (kF4Waves * Q * 128);
 #pragma unroll
     for (int p = 0; p < Q; ++p)
       *reinterpret_cast<float2 *>(rbuf + ((wave * Q + p) * 64 + lane) * 2) =
@@ -452,7 +467,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     // ---- every output sums the K ranges in ascending order, then the planes; -2 alpha: the codes are -t/2
     if (tid < RG * 128) {
       const int c = tid & 7, nrow = (tid >> 3) & 15, rg = tid >> 7;
-      const int go = gran0 + rg;
+      const int go = gran0 + r * RG + rg;
       const int row = (go >> 1) * 32 + (go & 1) * 16 + nrow;
       if (c < B && go < n_gran && row < l_m) {
         const float *src = rbuf + ((rg * KS) * Q * 64 + nrow + 16 * (c >> 1)) * 2 + (c & 1);
@@ -467,13 +482,34 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
         Y[(int64_t)row * ldy + c] = y;
       }
     }
+  };
+  if constexpr (!MR) {
+    round_body(0, ring, offv, entv, fast, al, [] {});
+  } else {
+    Ring ringN;
+    uint32_t offN[Q], entN[Q];
+    float alN[Q];
+    bool fastN = true;
+    for (int r = 0; r < rounds; ++r) {  // uniform
+      // requests of the next round (of the last granule again when there is none: same number of requests)
+      load_ring(min(gran0 + (r + 1) * RG + rgi, n_gran - 1), ringN, offN);
+      load_alpha(r + 1, alN);
+      round_body(r, ring, offv, entv, fast, al, [&] { load_entries(offN, entN, fastN); });
+      ring = ringN;
+      fast = fastN;
+#pragma unroll
+      for (int p = 0; p < Q; ++p) {
+        offv[p] = offN[p];
+        entv[p] = entN[p];
+        al[p] = alN[p];
+      }
+    }
   }
 }
 
-// Picks the decomposition: PW word pairs per wave (at most PMAX), KS K ranges, RG granules per workgroup; false
-// when the kernel does not apply to the call (a layer with more 16-row pieces than one round of workgroups takes
-// goes to the other kernels).
-inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
+// Picks the decomposition: PW word pairs per wave (at most PMAX), KS K ranges, RG granules per workgroup and
+// round, and the number of rounds (at most one workgroup per CU); false when the kernel does not apply to the call.
+inline bool f4_plan(const DevLayer &D, int B, int PMAX, int PMAX_MR, F4Plan *out) {
   if (B < 1 || B > kF4MaxB || D.J != 1 || D.spr > kF4MaxSpr) return false;
   const int spr_pad = 2 * ((D.spr + 1) / 2);  // whole word pairs
   // raw X (with its column padding) and the operands of the whole K range share one area; scales next to it
@@ -488,13 +524,17 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
   for (int pw = PMAX; pw >= 1; --pw) {
     const int ks = (pairs + pw - 1) / pw;
     if (ks > kF4Waves) break;
-    const int rg = min(kF4Waves / ks, 8);  // at most 8 x 128 outputs per workgroup: one per thread
+    const int rg = min(kF4Waves / ks, 8);  // at most 8 x 128 outputs per workgroup and round: one per thread
     const int wgs = (n_gran + rg - 1) / rg;
-    if (wgs > kSplitMaxGroups) continue;  // one workgroup per CU, one piece per wave
-    const int cost = (pw + 2) * 1024 - wgs;  // time of a wave; among equals, more workgroups
+    const int grid = min(wgs, kSplitMaxGroups);
+    const int rounds = (wgs + grid - 1) / grid;
+    if (rounds > 1 && pw > PMAX_MR) continue;  // the requests of the next round need registers too
+    // time of a wave: a fixed part, then per round its pairs and the exchange of the partial sums; among equals,
+    // more workgroups
+    const int cost = (4 + rounds * (pw + 2)) * 1024 - grid;
     if (cost < best_cost) {
       best_cost = cost;
-      best = F4Plan{pw, ks, rg, wgs};
+      best = F4Plan{pw, ks, rg, grid, rounds};
     }
   }
   if (best_cost == (1 << 30)) return false;
@@ -502,7 +542,14 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, F4Plan *out) {
   return true;
 }
 
-template <int Q, int PMAX>
+// pairs per wave: what fits 128 registers, without and with the words of a round requested ahead (more tables
+// need more temporaries, a field that straddles two dwords a larger set of words per pair)
+constexpr int f4_pmax(int Q) { return Q == 1 ? 8 : (Q == 2 ? 6 : (Q == 3 ? 4 : 2)); }
+constexpr int f4_pmax_mr(int Q, int nibt) {
+  return Q == 1 ? (nibt == 1 ? 6 : 4) : Q == 2 ? (nibt == 3 ? 3 : 4) : Q == 3 ? (nibt == 3 ? 2 : 3) : 2;
+}
+
+template <int Q>
 int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y, int64_t ldy, const F4Plan &P,
                   hipStream_t st) {
   const uint16_t *Xh = static_cast<const uint16_t *>(X);
@@ -512,11 +559,20 @@ int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y
     kq_tab |= (uint64_t)(w % P.KS) << (4 * w);
     rg_tab |= (uint64_t)((w / P.KS) & 15) << (4 * w);
   }
-  switch (D.nib) {
-    case 1: hipLaunchKernelGGL((spmm_f4_kernel<Q, 1, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
-    case 2: hipLaunchKernelGGL((spmm_f4_kernel<Q, 2, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
-    case 3: hipLaunchKernelGGL((spmm_f4_kernel<Q, 3, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
-    default: hipLaunchKernelGGL((spmm_f4_kernel<Q, 4, PMAX>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, kq_tab, rg_tab); break;
+  if (P.rounds == 1) {
+    switch (D.nib) {
+      case 1: hipLaunchKernelGGL((spmm_f4_kernel<Q, 1, f4_pmax(Q), false>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, 1, kq_tab, rg_tab); break;
+      case 2: hipLaunchKernelGGL((spmm_f4_kernel<Q, 2, f4_pmax(Q), false>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, 1, kq_tab, rg_tab); break;
+      case 3: hipLaunchKernelGGL((spmm_f4_kernel<Q, 3, f4_pmax(Q), false>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, 1, kq_tab, rg_tab); break;
+      default: hipLaunchKernelGGL((spmm_f4_kernel<Q, 4, f4_pmax(Q), false>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, 1, kq_tab, rg_tab); break;
+    }
+  } else {
+    switch (D.nib) {
+      case 1: hipLaunchKernelGGL((spmm_f4_kernel<Q, 1, f4_pmax_mr(Q, 1), true>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
+      case 2: hipLaunchKernelGGL((spmm_f4_kernel<Q, 2, f4_pmax_mr(Q, 2), true>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
+      case 3: hipLaunchKernelGGL((spmm_f4_kernel<Q, 3, f4_pmax_mr(Q, 3), true>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
+      default: hipLaunchKernelGGL((spmm_f4_kernel<Q, 4, f4_pmax_mr(Q, 4), true>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, P.rounds, kq_tab, rg_tab); break;
+    }
   }
   return xorenc_internal_check_launch();
 }
@@ -528,11 +584,9 @@ bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ld
                    hipStream_t st, int32_t *rc) {
   if (x_dtype != XORENC_X_BF16 || D.J != 1) return false;
   if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
-  // pairs per wave: what fits 128 registers
-  constexpr int PMAX = Q == 1 ? 8 : (Q == 2 ? 6 : (Q == 3 ? 4 : 2));
   F4Plan P;
-  if (!f4_plan(D, B, PMAX, &P)) return false;
-  *rc = launch_f4<Q, PMAX>(D, X, ldx, B, Y, ldy, P, st);
+  if (!f4_plan(D, B, f4_pmax(Q), f4_pmax_mr(Q, D.nib), &P)) return false;
+  *rc = launch_f4<Q>(D, X, ldx, B, Y, ldy, P, st);
   return true;
 }
 
