@@ -1,5 +1,5 @@
 // Streaming variant of the fused decrypt + patch + mask + dequantise + W X kernel for bf16 X with at most
-// kF4MaxB columns (arXiv 1905.10138, Sections 3.1-3.2 for the decode, Fig. 1 for the product).  Included by the
+// four columns, or at most eight on layers tall enough for several rounds (arXiv 1905.10138, Sections 3.1-3.2 for the decode, Fig. 1 for the product).  Included by the
 // per-Q instantiation units next to the other fused kernels.
 //
 // With so few columns the product is bound by the compressed stream, so the kernel is built around the number
@@ -46,7 +46,9 @@ typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(2))) short s16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int kF4MaxB = 4;                  // beyond that the conversion of X costs more than the kernel saves
+constexpr int kF4MaxB = 8;                  // the 16 rows of the X operand: two terms of eight columns
+constexpr int kF4MaxBOneRound = 4;          // beyond that the conversion of X costs more than one round saves ...
+constexpr int kF4MinRoundsWide = 6;         // ... and pays from about this many rounds on
 constexpr int kF4Waves = 16;
 constexpr int kF4XBytes = 64 * 1024 + 256;  // raw X, then the X operands, then the partial sums
 constexpr int kF4MaxSpr = 256;              // 16 waves x 8 pairs x 2 words
@@ -69,6 +71,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   constexpr int NT = kF4Waves * 64;
   constexpr bool two_dw = NIBT == 3;
   constexpr int XR = 4;   // rows of X per thread, column and trip on the element-wise path
+  constexpr int MAXB = MR ? kF4MaxB : kF4MaxBOneRound;
   __shared__ __attribute__((aligned(16))) uint8_t xs[kF4XBytes];
   __shared__ __attribute__((aligned(16))) uint8_t scl[kF4SclBytes];        // scale bytes: (half-word, row of the A operand)
   __shared__ __attribute__((aligned(16))) uint32_t lut[NIBT * 2048];       // entry (table, value, half): four dwords
@@ -104,9 +107,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   const __amdgpu_buffer_rsrc_t xrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(X), 0, x_extent, kRsrcFlags);
   const uint32_t row_bytes = (uint32_t)(ldx * 2);
-  uint16_t xv[kF4MaxB][XR];
+  uint16_t xv[MAXB][XR];
 #pragma unroll
-  for (int c = 0; c < kF4MaxB; ++c)
+  for (int c = 0; c < MAXB; ++c)
     if (c < B)  // uniform
 #pragma unroll
       for (int i = 0; i < XR; ++i)
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
 
   // ---- raw X into LDS, column-major: element (k, c) at c*CS + 2k
 #pragma unroll
-  for (int c = 0; c < kF4MaxB; ++c)
+  for (int c = 0; c < MAXB; ++c)
     if (c < B)  // uniform
 #pragma unroll
       for (int i = 0; i < XR; ++i)
@@ -233,7 +236,10 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   // half-words of the word that pads an odd number of words to whole pairs are written as zeros.
   const int nb = 2 * l_spr, nb_pad = 4 * ((l_spr + 1) >> 1);
   int cv_c, cv_blk;
-  if (B >= 3) {  // lanes c fastest, then blk%4: the 16-byte reads of 16 lanes fall into 16 different bank groups
+  if (MR && B >= 5) {
+    cv_c = tid & 7;
+    cv_blk = tid >> 3;
+  } else if (B >= 3) {  // lanes c fastest, then blk%4: the 16-byte reads of 16 lanes fall into 16 different bank groups
     cv_c = tid & 3;
     cv_blk = tid >> 2;
   } else {
@@ -515,7 +521,7 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, int PMAX_MR, F4Plan *out
   // raw X (with its column padding) and the operands of the whole K range share one area; scales next to it
   if ((int64_t)spr_pad * 128 * B + 256 > kF4XBytes || 4 * spr_pad * B + 16 > kF4SclBytes) return false;
   // one conversion item (half-word, column) per thread
-  const int items = 2 * spr_pad * (B >= 3 ? 4 : B);
+  const int items = 2 * spr_pad * (B >= 5 ? 8 : (B >= 3 ? 4 : B));
   if (items > kF4Waves * 64) return false;
   const int pairs = (D.spr + 1) / 2;
   const int n_gran = 2 * D.nrb;
@@ -538,6 +544,7 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, int PMAX_MR, F4Plan *out
     }
   }
   if (best_cost == (1 << 30)) return false;
+  if (B > kF4MaxBOneRound && best.rounds < kF4MinRoundsWide) return false;
   *out = best;
   return true;
 }
@@ -577,12 +584,15 @@ int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y
   return xorenc_internal_check_launch();
 }
 
-// bf16 X with at most kF4MaxB columns, slices of one 64-bit word, one dword of encrypted bits per lane (two
+// bf16 X with at most four columns (eight on tall layers), slices of one 64-bit word, one dword of encrypted bits per lane (two
 // for 17..24 bits)
 template <int Q>
 bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
-                   hipStream_t st, int32_t *rc) {
+                   int x_fast, hipStream_t st, int32_t *rc) {
   if (x_dtype != XORENC_X_BF16 || D.J != 1) return false;
+  // eight columns in 16-byte aligned rows have a kernel that streams them without a conversion (measured on a
+  // 65536 x 4096 layer: 29.8 against 32.6 us; five to seven columns 29 against 42-45 us with the other kernels)
+  if (B > kF4MaxBOneRound && x_fast) return false;
   if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
   F4Plan P;
   if (!f4_plan(D, B, f4_pmax(Q), f4_pmax_mr(Q, D.nib), &P)) return false;
