@@ -75,7 +75,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
   __shared__ __attribute__((aligned(16))) uint8_t xs[kF4XBytes];
   __shared__ __attribute__((aligned(16))) uint8_t scl[kF4SclBytes];        // scale bytes: (half-word, row of the A operand)
   __shared__ __attribute__((aligned(16))) uint32_t lut[NIBT * 2048];       // entry (table, value, half): four dwords
-  __shared__ __attribute__((aligned(16))) uint32_t flips[kF4Waves * 256];  // per wave: four dwords per lane
+  // patch flips are scattered for FG word pairs at a time: per wave and pair four dwords per lane
+  constexpr int FG = NIBT <= 2 ? 4 : 2;  // (larger tables leave room for fewer)
+  __shared__ __attribute__((aligned(16))) uint32_t flips[kF4Waves * 256 * FG];
 
   const uint8_t *const l_enc = L.enc;
   const uint32_t *const l_mask32 = L.mask32;
@@ -210,8 +212,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     }
   }
   // ---- the wave's flip area starts (and is left) zeroed
-  uint32_t *const myflips = flips + wave * 256;
-  *reinterpret_cast<u32x4 *>(myflips + lane * 4) = u32x4{0u, 0u, 0u, 0u};
+  uint32_t *const myflips = flips + wave * 256 * FG;
+#pragma unroll
+  for (int s = 0; s < FG; ++s) *reinterpret_cast<u32x4 *>(myflips + s * 256 + lane * 4) = u32x4{0u, 0u, 0u, 0u};
 
   // ---- raw X into LDS, column-major: element (k, c) at c*CS + 2k
 #pragma unroll
@@ -388,74 +391,96 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
         f_addr[p] = ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2);
         f_val[p] = 8u << (((v >> 2) & 7u) << 2);
       }
+      uint8_t *const fl = reinterpret_cast<uint8_t *>(myflips);
+      // where an entry v = (row%32) << 6 | bit goes inside the flip area of its unit, and the bit it flips
+      auto flip_addr = [](uint32_t v) { return ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2); };
+      auto flip_val = [](uint32_t v) { return 8u << (((v >> 2) & 7u) << 2); };
 #pragma clang loop unroll(full)
-      for (int pp = 0; pp < PMAX; ++pp) {
-        if (pp < npw) {  // uniform; a break here would make the trip count a run-time value and keep the loop rolled
-          const uint32_t mw = ring.mw[pp];
+      for (int g0 = 0; g0 < PMAX; g0 += FG) {
+        if (g0 < npw) {  // uniform; a break here would make the trip count a run-time value and keep the loop rolled
 #pragma unroll
           for (int p = 0; p < Q; ++p) {
-            uint32_t x;
-            if (two_dw)
-              x = __builtin_amdgcn_alignbit(ring.e1[pp][p], ring.e0[pp][p], sh);
-            else
-              x = ring.e0[pp][p] >> sh;
-            u32x4 sg;
-            {
-              const uint32_t i0 = NIBT == 1 ? __builtin_amdgcn_ubfe(x, 0, last_bits) : (x & 255u);
-              sg = *reinterpret_cast<const u32x4 *>(lut_lane + i0 * 32u);
-            }
-            if constexpr (NIBT >= 2) {
-              const uint32_t i1 = NIBT == 2 ? __builtin_amdgcn_ubfe(x, 8, last_bits) : ((x >> 8) & 255u);
-              sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 8192u + i1 * 32u);
-            }
-            if constexpr (NIBT >= 3) {
-              const uint32_t i2 = NIBT == 3 ? __builtin_amdgcn_ubfe(x, 16, last_bits) : ((x >> 16) & 255u);
-              sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 16384u + i2 * 32u);
-            }
-            if constexpr (NIBT >= 4) {
-              const uint32_t i3 = __builtin_amdgcn_ubfe(x, 24, last_bits);
-              sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 24576u + i3 * 32u);
-            }
-            // patch flips of the pair's two units: entries [pa, pb) of the list, the first unit's end at pm
+            // ---- patch flips of the group's 2 FG units (words w_lo + 2 g0 ..): list ends ub[k] relative to the
+            // first entry of the wave's range; entry j belongs to unit t = number of ends <= j, whose 512 bytes of
+            // the flip area start at 512 t
             const uint32_t base = __builtin_amdgcn_readlane(offv[p], 0);
-            const uint32_t pa = __builtin_amdgcn_readlane(offv[p], 2 * pp) - base;
-            const uint32_t pm = __builtin_amdgcn_readlane(offv[p], 2 * pp + 1) - base;
-            const uint32_t pb = __builtin_amdgcn_readlane(offv[p], 2 * pp + 2) - base;
-            if (pb > pa) {  // uniform
-              uint8_t *const fl = reinterpret_cast<uint8_t *>(myflips);
+            uint32_t ub[2 * FG + 1];
+#pragma unroll
+            for (int k = 0; k <= 2 * FG; ++k)
+              ub[k] = __builtin_amdgcn_readlane(offv[p], (2 * g0 + k) < 2 * PMAX ? (2 * g0 + k) : 2 * PMAX) - base;
+            if (ub[2 * FG] > ub[0]) {  // uniform
               if (fast) {
-                if (f_mine[p] && (uint32_t)lane >= pa && (uint32_t)lane < pb)
-                  __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(fl + f_addr[p] + ((uint32_t)lane >= pm ? 512u : 0u)),
-                                         f_val[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                if (f_mine[p] && (uint32_t)lane >= ub[0] && (uint32_t)lane < ub[2 * FG]) {
+                  uint32_t t = 0;
+#pragma unroll
+                  for (int k = 1; k < 2 * FG; ++k) t += (uint32_t)lane >= ub[k] ? 1u : 0u;
+                  __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(fl + f_addr[p] + t * 512u), f_val[p],
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                }
               } else {
-                for (uint32_t j0 = pa; j0 < pb; j0 += 64u) {  // uniform
+                for (uint32_t j0 = ub[0]; j0 < ub[2 * FG]; j0 += 64u) {  // uniform
                   const uint32_t j = j0 + (uint32_t)lane;
-                  if (j < pb) {
+                  if (j < ub[2 * FG]) {
                     const uint32_t v = (l_patch + base)[j];
-                    if ((int)(v >> 10) == h)
-                      __hip_atomic_fetch_xor(
-                          reinterpret_cast<uint32_t *>(fl + ((((v >> 6) & 15u) + ((v >> 1) & 16u)) << 4) + ((v & 3u) << 2) +
-                                                       (j >= pm ? 512u : 0u)),
-                          8u << (((v >> 2) & 7u) << 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    if ((int)(v >> 10) == h) {
+                      uint32_t t = 0;
+#pragma unroll
+                      for (int k = 1; k < 2 * FG; ++k) t += j >= ub[k] ? 1u : 0u;
+                      __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(fl + flip_addr(v) + t * 512u), flip_val(v),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    }
                   }
                 }
               }
-              u32x4 *fp = reinterpret_cast<u32x4 *>(fl + flip_lane);
-              sg ^= *fp;
-              *fp = u32x4{0u, 0u, 0u, 0u};
             }
-            i32x8 bw;
-            bw[0] = (int)((mw & 0x11111111u) | sg[0]);
-            bw[1] = (int)((mw & 0x22222222u) | sg[1]);
-            bw[2] = (int)((mw & 0x44444444u) | sg[2]);
-            bw[3] = (int)(((mw >> 3) & 0x11111111u) | sg[3]);
-            bw[4] = bw[5] = bw[6] = bw[7] = 0;
-            const int sa = (int)xsc[pp >> 2];
-            switch (pp & 3) {  // the byte of the scale register is part of the instruction
-              case 0: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 0, sa, 0, 127); break;
-              case 1: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 1, sa, 0, 127); break;
-              case 2: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 2, sa, 0, 127); break;
-              default: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xop[pp], bw, acc[p], 0, 4, 3, sa, 0, 127); break;
+            // ---- the group's pairs
+#pragma unroll
+            for (int s = 0; s < FG; ++s) {
+              const int pp = g0 + s;
+              if (pp < PMAX && pp < npw) {  // uniform
+                const uint32_t mw = ring.mw[pp < PMAX ? pp : 0];
+                uint32_t x;
+                if (two_dw)
+                  x = __builtin_amdgcn_alignbit(ring.e1[pp < PMAX ? pp : 0][p], ring.e0[pp < PMAX ? pp : 0][p], sh);
+                else
+                  x = ring.e0[pp < PMAX ? pp : 0][p] >> sh;
+                u32x4 sg;
+                {
+                  const uint32_t i0 = NIBT == 1 ? __builtin_amdgcn_ubfe(x, 0, last_bits) : (x & 255u);
+                  sg = *reinterpret_cast<const u32x4 *>(lut_lane + i0 * 32u);
+                }
+                if constexpr (NIBT >= 2) {
+                  const uint32_t i1 = NIBT == 2 ? __builtin_amdgcn_ubfe(x, 8, last_bits) : ((x >> 8) & 255u);
+                  sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 8192u + i1 * 32u);
+                }
+                if constexpr (NIBT >= 3) {
+                  const uint32_t i2 = NIBT == 3 ? __builtin_amdgcn_ubfe(x, 16, last_bits) : ((x >> 16) & 255u);
+                  sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 16384u + i2 * 32u);
+                }
+                if constexpr (NIBT >= 4) {
+                  const uint32_t i3 = __builtin_amdgcn_ubfe(x, 24, last_bits);
+                  sg ^= *reinterpret_cast<const u32x4 *>(lut_lane + 24576u + i3 * 32u);
+                }
+                if (ub[2 * s + 2] > ub[2 * s]) {  // uniform: the pair has entries; the area is left zeroed
+                  u32x4 *fp = reinterpret_cast<u32x4 *>(fl + s * 1024 + flip_lane);
+                  sg ^= *fp;
+                  *fp = u32x4{0u, 0u, 0u, 0u};
+                }
+                i32x8 bw;
+                bw[0] = (int)((mw & 0x11111111u) | sg[0]);
+                bw[1] = (int)((mw & 0x22222222u) | sg[1]);
+                bw[2] = (int)((mw & 0x44444444u) | sg[2]);
+                bw[3] = (int)(((mw >> 3) & 0x11111111u) | sg[3]);
+                bw[4] = bw[5] = bw[6] = bw[7] = 0;
+                const int sa = (int)xsc[(pp < PMAX ? pp : 0) >> 2];
+                const i32x8 xo = xop[pp < PMAX ? pp : 0];
+                switch (pp & 3) {  // the byte of the scale register is part of the instruction
+                  case 0: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xo, bw, acc[p], 0, 4, 0, sa, 0, 127); break;
+                  case 1: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xo, bw, acc[p], 0, 4, 1, sa, 0, 127); break;
+                  case 2: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xo, bw, acc[p], 0, 4, 2, sa, 0, 127); break;
+                  default: acc[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(xo, bw, acc[p], 0, 4, 3, sa, 0, 127); break;
+                }
+              }
             }
           }
         }
