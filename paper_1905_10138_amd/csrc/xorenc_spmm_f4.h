@@ -48,7 +48,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kF4MaxB = 8;                  // the 16 rows of the X operand: two terms of eight columns
 constexpr int kF4MaxBOneRound = 4;          // beyond that the conversion of X costs more than one round saves ...
-constexpr int kF4MinRoundsWide = 6;         // ... and pays from about this many rounds on
+constexpr int kF4MinRoundsWide = 4;         // ... and pays from this many rounds on (measured, 4096 columns of W)
 constexpr int kF4Waves = 16;
 constexpr int kF4XBytes = 64 * 1024 + 256;  // raw X, then the X operands, then the partial sums
 constexpr int kF4MaxSpr = 256;              // 16 waves x 8 pairs x 2 words
@@ -559,7 +559,9 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, int PMAX_MR, F4Plan *out
     const int wgs = (n_gran + rg - 1) / rg;
     const int grid = min(wgs, kSplitMaxGroups);
     const int rounds = (wgs + grid - 1) / grid;
-    if (rounds > 1 && pw > PMAX_MR) continue;  // the requests of the next round need registers too
+    // the kernel variant that walks over rounds also serves more than four columns; its requests of the next round
+    // need registers too
+    if ((rounds > 1 || B > kF4MaxBOneRound) && pw > PMAX_MR) continue;
     // time of a wave: a fixed part, then per round its pairs and the exchange of the partial sums; among equals,
     // more workgroups
     const int cost = (4 + rounds * (pw + 2)) * 1024 - grid;
@@ -591,7 +593,7 @@ int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y
     kq_tab |= (uint64_t)(w % P.KS) << (4 * w);
     rg_tab |= (uint64_t)((w / P.KS) & 15) << (4 * w);
   }
-  if (P.rounds == 1) {
+  if (P.rounds == 1 && B <= kF4MaxBOneRound) {
     switch (D.nib) {
       case 1: hipLaunchKernelGGL((spmm_f4_kernel<Q, 1, f4_pmax(Q), false>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, 1, kq_tab, rg_tab); break;
       case 2: hipLaunchKernelGGL((spmm_f4_kernel<Q, 2, f4_pmax(Q), false>), grid, block, 0, st, D, Xh, ldx, B, Y, ldy, P.PW, P.KS, P.RG, 1, kq_tab, rg_tab); break;
@@ -616,7 +618,8 @@ bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ld
                    int x_fast, hipStream_t st, int32_t *rc) {
   if (x_dtype != XORENC_X_BF16 || D.J != 1) return false;
   // eight columns in 16-byte aligned rows have a kernel that streams them without a conversion (measured on a
-  // 65536 x 4096 layer: 29.8 against 32.6 us; five to seven columns 29 against 42-45 us with the other kernels)
+  // 65536 x 4096 layer: 29.8 against 32.6 us; five to seven columns 29 against 42-45 us with the other kernels,
+  // 19 against 23 us at 32768 rows, 15 against 13 us at 16384 rows)
   if (B > kF4MaxBOneRound && x_fast) return false;
   if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
   F4Plan P;
