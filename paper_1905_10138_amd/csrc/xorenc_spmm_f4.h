@@ -1,5 +1,5 @@
 // Streaming variant of the fused decrypt + patch + mask + dequantise + W X kernel for bf16 X with at most
-// four columns, or at most eight on layers tall enough for several rounds (arXiv 1905.10138, Sections 3.1-3.2 for the decode, Fig. 1 for the product).  Included by the
+// two columns, or at most eight on layers tall enough for several rounds (arXiv 1905.10138, Sections 3.1-3.2 for the decode, Fig. 1 for the product).  Included by the
 // per-Q instantiation units next to the other fused kernels.
 //
 // With so few columns the product is bound by the compressed stream, so the kernel is built around the number
@@ -47,7 +47,7 @@ typedef __attribute__((ext_vector_type(2))) short s16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kF4MaxB = 8;                  // the 16 rows of the X operand: two terms of eight columns
-constexpr int kF4MaxBOneRound = 4;          // beyond that the conversion of X costs more than one round saves ...
+constexpr int kF4MaxBOneRound = 2;          // beyond that the other kernels are faster on one round (measured) ...
 constexpr int kF4MinRoundsWide = 4;         // ... and pays from this many rounds on (measured, 4096 columns of W)
 constexpr int kF4Waves = 16;
 constexpr int kF4XBytes = 64 * 1024 + 256;  // raw X, then the X operands, then the partial sums
@@ -559,7 +559,7 @@ inline bool f4_plan(const DevLayer &D, int B, int PMAX, int PMAX_MR, F4Plan *out
     const int wgs = (n_gran + rg - 1) / rg;
     const int grid = min(wgs, kSplitMaxGroups);
     const int rounds = (wgs + grid - 1) / grid;
-    // the kernel variant that walks over rounds also serves more than four columns; its requests of the next round
+    // the kernel variant that walks over rounds also serves more than two columns; its requests of the next round
     // need registers too
     if ((rounds > 1 || B > kF4MaxBOneRound) && pw > PMAX_MR) continue;
     // time of a wave: a fixed part, then per round its pairs and the exchange of the partial sums; among equals,
@@ -611,7 +611,7 @@ int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y
   return xorenc_internal_check_launch();
 }
 
-// bf16 X with at most four columns (eight on tall layers), slices of one 64-bit word, one dword of encrypted bits per lane (two
+// bf16 X with at most two columns (eight on tall layers), slices of one 64-bit word, one dword of encrypted bits per lane (two
 // for 17..24 bits)
 template <int Q>
 bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
