@@ -273,12 +273,16 @@ XORENC_API int32_t xorenc_decode(const xorenc_layer *layer, int32_t out_kind, vo
  *   Y  DEV float, row-major m x B, leading dimension ldy >= B; overwritten.
  * Accumulation is fp32; alpha is applied in fp32 after the contraction of each plane.  fp32 X is
  * split exactly into three bf16 terms, so the fp32 path keeps fp32 accuracy on the matrix cores.
- * One kernel launch per call, and the same bits in Y for the same inputs on every call: sums are formed in a
- * fixed order.  For small layers the launch splits the reduction dimension over several workgroups per
- * output tile; their partial tiles meet in a scratch area that the library keeps in device memory on every
- * GPU (about 16 MiB, four slots taken in turn by successive calls), and the workgroup that finishes last adds
- * them in the order of their slice ranges.  At most four such calls may therefore overlap on one GPU (on
- * different streams; calls on one stream never overlap); a fifth could read another call's partial sums.
+ * The same bits in Y for the same inputs on every call: sums are formed in a fixed order.  One kernel launch per
+ * call, two when the rows of X do not start on 16-byte boundaries (ldx not a multiple of 8 bf16 / 4 fp32 values, or
+ * such a base address) and X has at least five columns and at most 4 MiB with its rows padded to whole 16-byte
+ * pieces: a first kernel then copies X into a staging area inside the library, and the product reads the copy
+ * (the fast kernels fetch X in 16-byte pieces).  For small layers the launch splits the reduction dimension over
+ * several workgroups per output tile; their partial tiles meet in a scratch area, and the workgroup that finishes
+ * last adds them in the order of their slice ranges.  Staging and scratch areas live in device memory that the
+ * library keeps on every GPU (about 32 MiB, four slots taken in turn by successive calls).  At most four calls
+ * that use a slot may therefore overlap on one GPU (on different streams; calls on one stream never overlap); a
+ * fifth could read another call's partial sums or copy of X.
  * Nothing is allocated by the call.
  */
 XORENC_API int32_t xorenc_spmm(const xorenc_layer *layer, const void *X, int32_t x_dtype, int64_t ldx, int32_t B, float *Y,

@@ -611,19 +611,24 @@ int32_t launch_f4(const DevLayer &D, const void *X, int64_t ldx, int B, float *Y
   return xorenc_internal_check_launch();
 }
 
-// bf16 X with at most two columns (eight on tall layers), slices of one 64-bit word, one dword of encrypted bits per lane (two
-// for 17..24 bits)
-template <int Q>
-bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
-                   int x_fast, hipStream_t st, int32_t *rc) {
+// whether the few-column kernel takes the call (the entry point asks before it decides how X is passed on)
+inline bool f4_applies(const DevLayer &D, int32_t x_dtype, int B, int x_fast, F4Plan *plan) {
   if (x_dtype != XORENC_X_BF16 || D.J != 1) return false;
   // eight columns in 16-byte aligned rows have a kernel that streams them without a conversion (measured on a
   // 65536 x 4096 layer: 29.8 against 32.6 us; five to seven columns 29 against 42-45 us with the other kernels,
   // 19 against 23 us at 32768 rows, 15 against 13 us at 16384 rows)
   if (B > kF4MaxBOneRound && x_fast) return false;
   if ((D.n_in & (D.n_in - 1)) != 0 && D.nib != 3) return false;
+  return f4_plan(D, B, f4_pmax(D.q), f4_pmax_mr(D.q, D.nib), plan);
+}
+
+// bf16 X with at most two columns (eight on tall layers), slices of one 64-bit word, one dword of encrypted bits
+// per lane (two for 17..24 bits)
+template <int Q>
+bool dispatch_f4_q(const DevLayer &D, const void *X, int32_t x_dtype, int64_t ldx, int B, float *Y, int64_t ldy,
+                   int x_fast, hipStream_t st, int32_t *rc) {
   F4Plan P;
-  if (!f4_plan(D, B, f4_pmax(Q), f4_pmax_mr(Q, D.nib), &P)) return false;
+  if (D.q != Q || !f4_applies(D, x_dtype, B, x_fast, &P)) return false;
   *rc = launch_f4<Q>(D, X, ldx, B, Y, ldy, P, st);
   return true;
 }

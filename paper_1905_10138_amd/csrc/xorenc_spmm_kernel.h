@@ -191,7 +191,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && XFAST && !XF32) ? 2 : 1) void 
 
   // ---- buffer descriptors
   const int64_t row_bytes = ldx * ESZ;
-  const uint32_t x_extent = (uint32_t)((int64_t)(l_n - 1) * row_bytes + (int64_t)(B - col0) * ESZ);
+  // (16-byte fetches are range-checked dword by dword: an odd number of bf16 columns ends in the middle of a dword,
+  // which still has to count as inside; the two bytes behind it lie in the same aligned dword as the last element)
+  const uint32_t x_extent = ((uint32_t)((int64_t)(l_n - 1) * row_bytes + (int64_t)(B - col0) * ESZ) + (XFAST ? 3u : 0u)) &
+                            (XFAST ? ~3u : ~0u);
   const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t *>(static_cast<const uint8_t *>(Xv) + (int64_t)col0 * ESZ), 0, x_extent, kRsrcFlags);
   const __amdgpu_buffer_rsrc_t mrsrc = __builtin_amdgcn_make_buffer_rsrc(

@@ -255,6 +255,22 @@ def test_odd_leading_dimension_and_unaligned_rows():
     assert rel_fro(got, want) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("name,m,n,B,dtype,pad", [
+    # compact X whose rows do not start on 16-byte boundaries: copied to a padded staging area first
+    ("large_q1", 320, 1024, 33, "bf16", 0), ("large_q1", 320, 1024, 65, "bf16", 0), ("lstm", 130, 3000, 9, "bf16", 0),
+    ("large_q2", 96, 4096, 100, "bf16", 3), ("fc6", 97, 640, 7, "bf16", 0), ("fig1", 200, 448, 5, "bf16", 2),
+    ("tiny", 256, 256, 9, "f32", 0), ("tiny", 33, 70, 13, "f32", 2), ("lstm", 130, 3000, 21, "f32", 0),
+    # aligned rows, a last 16-byte piece with fewer columns (fetched whole; the extent of X ends inside a dword)
+    ("large_q1", 320, 1024, 33, "bf16", 7), ("large_q1", 320, 1024, 5, "bf16", 3), ("fig1", 200, 448, 71, "bf16", 1),
+    ("tiny", 33, 70, 5, "f32", 3), ("lstm", 130, 3000, 3, "bf16", 5),
+    # too large for the staging area (4 MiB with padded rows): the element-wise kernels
+    ("large_q2", 96, 4096, 530, "bf16", 0)])
+def test_rows_of_X_that_do_not_start_on_16_byte_boundaries(name, m, n, B, dtype, pad):
+    got, want = _run(name, m, n, B, dtype, ldx_pad=pad, every_output=(dtype == "bf16"))
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= TOL[dtype]
+
+
 def test_identity_X_reproduces_decoded_weights():
     """Y = W I = W: the fused path against the decode path, no oracle involved in the comparison."""
     import torch
