@@ -399,6 +399,8 @@ def wide_extra(xe, torch, dev, args, base_cfg, n_in=24):
         res[f"B{B}_tflops"] = r["tflops"]
         res[f"B{B}_compressed_gbs"] = r["compressed_gbs"]
         del runner
+    if not args.no_decode:
+        res["decode"] = decode_times(xe, torch, layer, args)
     return res
 
 

@@ -34,27 +34,6 @@ struct DevLayer {
 constexpr int kSplitTileFloats = 4096;  // largest output tile of a split launch (64 x 64)
 constexpr int kSplitMaxGroups = 256;    // workgroups of a split launch (one per CU)
 
-// T_{w,b}[v] for word w < J of a slice, b < nib, v < 256; entry ((w*nib + b)*256 + v) holds
-// {low 32 rows, high 32 rows} of the XOR of the columns 8b..8b+7 of M selected by the bits of v.
-static __device__ inline void build_xor_tables(uint32_t *lut, const DevLayer &L) {
-  for (int wb = 0; wb < L.J * L.nib; ++wb) {  // uniform: the columns of M come through scalar loads
-    const int w = wb / L.nib, b = wb % L.nib;
-    const uint32_t *clo = L.Mcol_lo + w * XORENC_MAX_N_IN + 8 * b;
-    const uint32_t *chi = L.Mcol_hi + w * XORENC_MAX_N_IN + 8 * b;
-    for (int v = threadIdx.x; v < 256; v += blockDim.x) {
-      uint32_t lo = 0, hi = 0;
-#pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if ((v >> t) & 1) {
-          lo ^= clo[t];
-          hi ^= chi[t];
-        }
-      lut[2 * (wb * 256 + v)] = lo;
-      lut[2 * (wb * 256 + v) + 1] = hi;
-    }
-  }
-}
-
 // field `e` (n_in bits at bit e*n_in) of the encrypted bit stream, seen as aligned dwords
 static __device__ inline uint32_t load_enc(const uint8_t *enc, int64_t e, int n_in) {
   const uint32_t *d = reinterpret_cast<const uint32_t *>(enc);
