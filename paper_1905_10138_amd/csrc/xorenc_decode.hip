@@ -165,17 +165,42 @@ __global__ __launch_bounds__(256) void decode_run_kernel(DevLayer L, void *__res
     if ((uint32_t)lane < etotal[p]) ent[p] = L.patch[ebase[p] + lane];
   }
   // ---- tables (shared by the four waves) and this wave's flip words
-  for (int w = 0; w < J; ++w)        // uniform
-    for (int b = 0; b < nib; ++b) {  // uniform
+  const int n_tab = J * nib;
+  if (n_tab < 3) {
+    for (int w = 0; w < J; ++w)        // uniform
+      for (int b = 0; b < nib; ++b) {  // uniform
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const uint32_t on = 0u - ((threadIdx.x >> t) & 1u);
+          lo ^= L.Mcol_lo[w * XORENC_MAX_N_IN + 8 * b + t] & on;
+          hi ^= L.Mcol_hi[w * XORENC_MAX_N_IN + 8 * b + t] & on;
+        }
+        lut[(w * nib + b) * 256 + threadIdx.x] = make_uint2(lo, hi);
+      }
+  } else {
+    // many tables: first the 16-entry tables of every four columns (two per table, behind the tables in LDS),
+    // then an entry is the XOR of two of those
+    uint2 *const quad = lut + n_tab * 256;
+    for (int e = threadIdx.x; e < n_tab * 32; e += 256) {  // entry e%16 of four-column table e/16
+      const int qt = e >> 4, v = e & 15, wb = qt >> 1;
+      const int w = wb / nib, b = wb - w * nib;             // (at most sixteen tables: small numbers)
+      const int c0 = w * XORENC_MAX_N_IN + 8 * b + 4 * (qt & 1);
       uint32_t lo = 0, hi = 0;
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const uint32_t on = 0u - ((threadIdx.x >> t) & 1u);
-        lo ^= L.Mcol_lo[w * XORENC_MAX_N_IN + 8 * b + t] & on;
-        hi ^= L.Mcol_hi[w * XORENC_MAX_N_IN + 8 * b + t] & on;
+      for (int t = 0; t < 4; ++t) {
+        const uint32_t on = 0u - ((uint32_t)(v >> t) & 1u);
+        lo ^= L.Mcol_lo[c0 + t] & on;
+        hi ^= L.Mcol_hi[c0 + t] & on;
       }
-      lut[(w * nib + b) * 256 + threadIdx.x] = make_uint2(lo, hi);
+      quad[e] = make_uint2(lo, hi);
     }
+    __syncthreads();
+    for (int wb = 0; wb < n_tab; ++wb) {  // uniform
+      const uint2 a = quad[wb * 32 + (threadIdx.x & 15)], c = quad[wb * 32 + 16 + (threadIdx.x >> 4)];
+      lut[wb * 256 + threadIdx.x] = make_uint2(a.x ^ c.x, a.y ^ c.y);
+    }
+  }
   if constexpr (DENSE) {
     uint32_t v = threadIdx.x;
     v = (v | (v << 12)) & 0x000F000Fu;
@@ -354,7 +379,8 @@ template <int Q, int KIND>
 void launch_decode_run(const DevLayer &D, void *out, int64_t ld, hipStream_t st) {
   const int runs_per_rb = (D.spr + 7) / 8;
   const int64_t runs = (int64_t)runs_per_rb * D.nrb;
-  const size_t lut_bytes = (size_t)D.J * D.nib * 256 * sizeof(uint2);
+  // the tables, and behind them the four-column tables they are built from when there are many
+  const size_t lut_bytes = (size_t)D.J * D.nib * (256 + 32) * sizeof(uint2);
   const dim3 grid((unsigned)((runs + 3) / 4)), block(256);
   if (D.J == 1)
     hipLaunchKernelGGL((decode_run_kernel<Q, KIND, false>), grid, block, lut_bytes, st, D, out, ld, runs_per_rb);
