@@ -1002,6 +1002,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
       if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
       return launch_spmm<2, Q, 2, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     }
+    if (B <= 8 && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (B <= 8 && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     // (small layers: 32-row tiles while they fit one round, see below; 4096 x 4096 at B = 32: 7.5 against 8.6 us)
     if (blocks == 1 && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
@@ -1019,6 +1020,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     if (D.J == 1 && small_layer) return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
+    if (B <= 8 && x_fast && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (B <= 8 && x_fast && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1 && x_fast && D.J == 1 && small_layer)
       return launch_spmm<1, Q, 1, false, 12, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
@@ -1035,6 +1037,7 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 3) {
     // (12 waves with one slice buffer: measured 13.2 against 18.9 us with 8 waves and two buffers, 6000 x 3000, B = 32)
+    if (B <= 8 && x_fast && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (B <= 8 && x_fast && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     // (32-row tiles on small layers: 6000 x 3000 at B = 32 9.8 against 12.3 us)
     if (x_fast && D.J == 1 && (int64_t)((D.nrb + 1) / 2) * blocks <= 128)
