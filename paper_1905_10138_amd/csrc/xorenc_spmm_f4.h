@@ -61,8 +61,8 @@ struct F4Plan {
 // kq_tab / rg_tab: four bits per wave, the wave's K range and its place among the RG granules of a round.
 // MR: a workgroup walks over `rounds` sets of RG granules (layers with more granules than one round of workgroups
 // takes).  X is converted and the tables are built once; the compressed words, patch offsets and scales of the next
-// round are requested before the current round's work (always the same number of requests, granule indices
-// clamped to the last one, so that the waits can count them), its patch entries after it.
+// round are requested before the current round's work (always the same number of requests, so that the waits
+// can count them: the last round asks for its own granule again), its patch entries after it.
 template <int Q, int NIBT, int PMAX, bool MR>
 __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, const uint16_t *__restrict__ X, int64_t ldx,
                                                                int B, float *__restrict__ Y, int64_t ldy, int PW, int KS,
@@ -522,8 +522,9 @@ __global__ __launch_bounds__(kF4Waves * 64) void spmm_f4_kernel(DevLayer L, cons
     float alN[Q];
     bool fastN = true;
     for (int r = 0; r < rounds; ++r) {  // uniform
-      // requests of the next round (of the last granule again when there is none: same number of requests)
-      load_ring(min(gran0 + (r + 1) * RG + rgi, n_gran - 1), ringN, offN);
+      // requests of the next round; in the last round of the current granule again (same number of requests,
+      // lines that are in the cache already, and not the next workgroup's granules from memory)
+      load_ring(min(gran0 + (r + 1 < rounds ? r + 1 : r) * RG + rgi, n_gran - 1), ringN, offN);
       load_alpha(r + 1, alN);
       round_body(r, ring, offv, entv, fast, al, [&] { load_entries(offN, entN, fastN); });
       ring = ringN;
