@@ -995,17 +995,30 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
       return launch_spmm<3, Q, 1, true, 4>(D, X, ldx, B, Y, ldy, x_fast, st);
   }
   const int blocks = (B + 31) / 32;
-  // at most 128 tiles of 64 rows (and 64 columns): 32-row tiles still run in one round of workgroups
-  const bool small_layer = (int64_t)((D.nrb + 1) / 2) * ((B + 63) / 64) <= 128;
+  // Small layers take 32-row tiles: twice the workgroups (still one round), half the accumulators and half the tile
+  // exchange per wave.  It pays while a wave's share of the reduction stays short (measured: up to eight slices
+  // per wave it wins, 2048 x 16384 at B = 64 14.4 against 16.8 us; at sixteen it loses, 8192 x 8192 19.7 against
+  // 16.6 us): slices per wave with 32-row tiles, nw waves and the split launch_spmm would choose.
+  auto rb1_slices_per_wave = [&](int nw, int col_groups) {
+    const int64_t tiles = (int64_t)D.nrb * col_groups;
+    if (tiles > kSplitMaxGroups) return 1 << 30;
+    int ks = 1;
+    if (tiles < kSplitMaxGroups) ks = max(1, min(min((D.spr + nw - 1) / nw, (int)(kSplitMaxGroups / tiles)), 4));
+    const int sps = (D.spr + ks - 1) / ks;
+    return (sps + nw - 1) / nw;
+  };
+  const bool small_wide = rb1_slices_per_wave(8, (B + 63) / 64) <= 8;    // 33 and more columns, eight waves
+  const bool small_block = rb1_slices_per_wave(12, blocks) <= 8;         // one column block, twelve waves
+  const bool small_narrow = rb1_slices_per_wave(12, 1) <= 12;            // at most eight columns
   if constexpr (Q == 1) {
     if (!x_fast) {
       if (blocks == 1) return launch_spmm<1, Q, 2, false, 16, 1, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
       return launch_spmm<2, Q, 2, false, 8, 2, 2>(D, X, ldx, B, Y, ldy, x_fast, st);
     }
-    if (B <= 8 && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (B <= 8 && D.J == 1 && small_narrow) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (B <= 8 && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     // (small layers: 32-row tiles while they fit one round, see below; 4096 x 4096 at B = 32: 7.5 against 8.6 us)
-    if (blocks == 1 && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (blocks == 1 && D.J == 1 && small_block) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     // 128-row tiles halve the number of times X is re-read; used once they still fill most of the chip.
     // Up to 256 of them run as eight-wave workgroups, one per CU, in a single round; more run as
@@ -1015,14 +1028,13 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     if (D.J == 1 && D.nib <= 2 && tiles128 > 256)
       return launch_spmm<2, Q, 4, false, 4, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (D.J == 1 && tiles128 >= 200) return launch_spmm<2, Q, 4, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
-    // small layers: 32-row tiles while they still fit one round (twice the workgroups, half the accumulators and
-    // half the tile exchange per wave; 2048 x 2048 at B = 64: 7.6 against 9.3 us, 4096 x 4096: 9.4 against 11.5 us)
-    if (D.J == 1 && small_layer) return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
+    // (small layers, see above; 2048 x 2048 at B = 64: 7.6 against 9.3 us, 4096 x 4096: 9.4 against 11.5 us)
+    if (D.J == 1 && small_wide) return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<2, Q, 2, false, 8, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 2) {
-    if (B <= 8 && x_fast && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (B <= 8 && x_fast && D.J == 1 && small_narrow) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (B <= 8 && x_fast && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
-    if (blocks == 1 && x_fast && D.J == 1 && small_layer)
+    if (blocks == 1 && x_fast && D.J == 1 && small_block)
       return launch_spmm<1, Q, 1, false, 12, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1 && x_fast) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (blocks == 1) return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
@@ -1037,10 +1049,10 @@ int32_t dispatch_spmm_q(const DevLayer &D, const void *X, int32_t x_dtype, int64
     return launch_spmm<2, Q, 1, false, 8, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
   } else if constexpr (Q == 3) {
     // (12 waves with one slice buffer: measured 13.2 against 18.9 us with 8 waves and two buffers, 6000 x 3000, B = 32)
-    if (B <= 8 && x_fast && D.J == 1 && small_layer) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
+    if (B <= 8 && x_fast && D.J == 1 && small_narrow) return launch_spmm<1, Q, 1, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (B <= 8 && x_fast && D.J == 1) return launch_spmm<1, Q, 2, false, 12, 1, 1, 1, true>(D, X, ldx, B, Y, ldy, x_fast, st);
     // (32-row tiles on small layers: 6000 x 3000 at B = 32 9.8 against 12.3 us)
-    if (x_fast && D.J == 1 && (int64_t)((D.nrb + 1) / 2) * blocks <= 128)
+    if (x_fast && D.J == 1 && small_block)
       return launch_spmm<1, Q, 1, false, 12, 1, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     if (x_fast) return launch_spmm<1, Q, 2, false, 12, 1, 1>(D, X, ldx, B, Y, ldy, x_fast, st);
     return launch_spmm<1, Q, 2, false>(D, X, ldx, B, Y, ldy, x_fast, st);
