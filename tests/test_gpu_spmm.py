@@ -149,7 +149,10 @@ def test_spmm_full_size_configs(name, B):
     ("large_q1", 16384, 256, 256, 8, None), ("large_q1", 16390, 200, 248, 8, None), ("large_q1", 12288, 320, 384, 16, None),
     ("large_q1", 12290, 256, 376, 24, None), ("large_q1", 16384, 192, 256, 8, 0.8),
     ("large_q2", 16390, 200, 136, 16, None), ("large_q2", 12810, 320, 64, 8, None), ("large_q2", 8200, 256, 256, 24, 0.85),
-    ("large_q1", 8192, 256, 256, 8, None), ("large_q1", 8200, 200, 328, 16, None), ("large_q2", 8200, 320, 136, 8, None)])
+    ("large_q1", 8192, 256, 256, 8, None), ("large_q1", 8200, 200, 328, 16, None), ("large_q2", 8200, 320, 136, 8, None),
+    # more than 256 tiles of 64 rows at 8, 16 and 32 aligned columns: four-wave workgroups, several per CU
+    ("large_q1", 20000, 512, 8, 8, None), ("large_q1", 40010, 200, 8, 16, 0.8), ("large_q1", 20000, 384, 16, 8, None),
+    ("large_q1", 18000, 320, 32, 16, None), ("large_q2", 17000, 256, 8, 8, None), ("large_q1", 33000, 130, 24, 8, 0.8)])
 def test_tall_matrix_many_columns(name, m, n, B, n_in, S):
     """Enough tiles to fill the chip once or twice: the launches with 128-row tiles (one plane) or 64-row tiles
     (two planes), with eight waves per workgroup up to 256 tiles and four waves, two workgroups per CU, above
